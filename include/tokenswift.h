@@ -1,0 +1,163 @@
+/*
+ * tokenswift.h -- C ABI of the MI355X (gfx950) decode-attention hot path of TokenSwift
+ * (arXiv 2502.18890): importance scoring and top-k selection for the dynamic partial KV
+ * cache, attention over that partial cache, and tree-masked verification attention over
+ * the full cache.
+ *
+ * General conventions
+ *   - Every pointer is a DEVICE pointer unless its comment says HOST.  The caller owns all
+ *     buffers, including the workspace; the library keeps no state between calls and never
+ *     allocates or frees device memory.
+ *   - bf16 arrays are passed as `const void*` (2-byte elements, IEEE bfloat16 bit patterns).
+ *     Outputs are fp32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work: outputs are valid once the stream has reached the call.  No call
+ *     synchronises.
+ *   - Every function returns a ts_status.  Arguments are validated on the host before
+ *     anything is launched; on any error nothing has been enqueued.  Device-resident index
+ *     arrays (chunk_idx) are NOT validated: chunk ids outside [0, n_chunks) are a caller
+ *     error with undefined results.
+ *   - head_dim is 128.  Rows of K and V (one token of one head) must be 16-byte aligned and
+ *     contiguous in the head dimension; heads and tokens are addressed through element
+ *     strides, so head-major [H_kv][N][128] and token-major [N][H_kv][128] caches both work.
+ *   - One call handles one layer, batch 1.
+ */
+#ifndef TOKENSWIFT_H
+#define TOKENSWIFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TS_OK = 0,
+    TS_ERR_NULL = -1,        /* a required pointer is NULL */
+    TS_ERR_SHAPE = -2,       /* sizes are inconsistent or out of range (N < 1, empty selection, ...) */
+    TS_ERR_UNSUPPORTED = -3, /* valid in principle, outside what the kernels cover (head_dim != 128, ...) */
+    TS_ERR_TREE = -4,        /* parent[] is not a forest in topological order */
+    TS_ERR_WORKSPACE = -5,   /* workspace missing or smaller than ts_workspace_bytes() */
+    TS_ERR_HIP = -6,         /* a HIP runtime call or kernel launch failed */
+    TS_ERR_ALIGN = -7        /* a pointer or stride breaks the 16-byte row alignment */
+} ts_status;
+
+/* Limits of the kernels. */
+#define TS_HEAD_DIM 128
+#define TS_MAX_TREE 64        /* tree nodes per call (one 64-bit ancestor mask per node) */
+#define TS_MAX_GROUP 8        /* query heads per KV head */
+#define TS_MAX_CHUNKS 8192    /* chunks per KV head that ts_topk_chunks can rank */
+
+/* One layer's KV cache, as the paper's C_full (Alg. 1): n_tokens cached (key, value) pairs
+ * for each of n_kv_heads heads.  Element (h, t, x) of K lives at
+ * ((const bf16*)k)[h*stride_head + t*stride_token + x]; V uses the same strides. */
+typedef struct {
+    const void *k;          /* bf16 */
+    const void *v;          /* bf16; may be NULL for ts_chunk_scores */
+    int64_t n_tokens;       /* N >= 1 (ts_tree_verify_attn also accepts 0: tree tokens only) */
+    int32_t n_kv_heads;
+    int32_t head_dim;       /* must be TS_HEAD_DIM */
+    int64_t stride_head;    /* elements; multiple of 8 */
+    int64_t stride_token;   /* elements; multiple of 8, >= head_dim */
+} ts_kv_view;
+
+enum { TS_OP_PARTIAL_ATTN = 1, TS_OP_TREE_VERIFY = 2 };
+
+/* Text for a ts_status (static storage, never NULL). */
+const char *ts_strerror(int status);
+
+/* ABI version: major*10000 + minor*100 + patch. */
+int ts_version(void);
+
+/*
+ * Bytes of device workspace that the split-K attention calls need for the given shape
+ * (0 on invalid arguments).  op is TS_OP_PARTIAL_ATTN (n_sel, chunk_size used; n_tree ignored)
+ * or TS_OP_TREE_VERIFY (n_tree used; n_sel, chunk_size ignored).  The workspace holds the
+ * per-split softmax partials (running max, sum of exponentials, unnormalised output) that a
+ * second kernel merges; its contents are scratch and need no initialisation.
+ */
+size_t ts_workspace_bytes(int op, int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree,
+                          int n_sel, int chunk_size);
+
+/*
+ * Importance scores of the cached keys (Sec. 3.3, "Importance Score of KV pairs", Eq. 2),
+ * averaged per chunk of `chunk_size` consecutive tokens:
+ *
+ *   scores[h][c] = scale * mean_{t in chunk c} sum_{j = h*g}^{(h+1)*g - 1} q[j] . K[h][t]
+ *
+ * with g = n_q_heads / kv->n_kv_heads (the GQA form of Eq. 2: the g query heads of a group
+ * are summed against the one shared key; g = 1 is plain Q K^T).  A short last chunk averages
+ * over its valid tokens.  chunk_size = 1 gives the per-token score of the paper.
+ *   q       bf16 [n_q_heads][128]: the query token that ranks the cache
+ *   scores  fp32 [n_kv_heads][ceil(N / chunk_size)]
+ * chunk_size: 1..1024.  Errors: NULL pointers, n_q_heads not a multiple of n_kv_heads,
+ * g > TS_MAX_GROUP, head_dim != 128, N < 1.
+ */
+int ts_chunk_scores(const ts_kv_view *kv, const void *q, int n_q_heads, int chunk_size,
+                    float scale, float *scores, void *stream);
+
+/*
+ * Chunk selection for the partial cache C_p = {C_full[0:|S|], Top-K_{|B|-|S|}(C_full)}
+ * (Alg. 1, prefill of C_p and "Dynamic KV Cache Update"; Sec. 3.3, "Dynamic KV Cache Updates"):
+ * per KV head, idx_out = [0, .., n_sink_chunks-1] followed by the k highest-scoring chunks
+ * among n_sink_chunks .. n_chunks-1, in order of decreasing score.  Equal scores rank by
+ * lower chunk index (-0 equals +0); NaN scores rank below every number, by index.
+ *   scores   fp32 [n_kv_heads][n_chunks]
+ *   idx_out  int32 [n_kv_heads][n_sink_chunks + k]
+ * Errors: n_chunks < 1 or > TS_MAX_CHUNKS, n_sink_chunks < 0, k < 0,
+ * n_sink_chunks + k > n_chunks, n_sink_chunks + k == 0.
+ */
+int ts_topk_chunks(const float *scores, int n_kv_heads, int n_chunks, int n_sink_chunks, int k,
+                   int32_t *idx_out, void *stream);
+
+/*
+ * Attention of the drafting forward pass over the partial cache (Alg. 1, "Multi-token
+ * Parallel Generation"): one query token per head, softmax(scale * q K_sel^T) V_sel over
+ * exactly the tokens of the listed chunks (chunk c = tokens [c*chunk_size,
+ * min(N, (c+1)*chunk_size))).  The chunks are read in place through the index list; nothing
+ * is copied.  A chunk listed twice counts twice.
+ *   q          bf16 [n_q_heads][128]
+ *   chunk_idx  int32 [n_kv_heads][n_sel]   (device; as written by ts_topk_chunks)
+ *   out        fp32 [n_q_heads][128]
+ *   lse        fp32 [n_q_heads], natural-log sum of exponentials of the scaled logits; nullable
+ *   workspace  >= ts_workspace_bytes(TS_OP_PARTIAL_ATTN, ...) bytes, 256-byte aligned
+ * chunk_size: multiple of 16, 16..1024.  Errors as above plus n_sel < 1.
+ */
+int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
+                       const int32_t *chunk_idx, int n_sel, int chunk_size, float scale,
+                       float *out, float *lse, void *workspace, size_t workspace_bytes,
+                       void *stream);
+
+/*
+ * Verification attention of the draft-token tree over the full cache (Alg. 1, "Parallel
+ * Verification"; App. E): row (node i, query head j) attends to every cached token of KV
+ * head j/g and to tree node u iff u == i or u is an ancestor of i.
+ *   q_tree          bf16 [n_tree][n_q_heads][128]
+ *   k_tree, v_tree  bf16 [n_tree][n_kv_heads][128]  (keys/values of the tree tokens; the cache
+ *                   holds accepted tokens only)
+ *   parent          HOST int32 [n_tree]: parent[i] == -1 (root) or 0 <= parent[i] < i;
+ *                   several roots are allowed.  Read during the call, not retained.
+ *   out             fp32 [n_tree][n_q_heads][128]
+ *   lse             fp32 [n_tree][n_q_heads]; nullable
+ *   workspace       >= ts_workspace_bytes(TS_OP_TREE_VERIFY, ...) bytes, 256-byte aligned
+ * n_tree: 1..TS_MAX_TREE.  kv->n_tokens may be 0 (then kv->k, kv->v may be NULL).
+ * Errors: TS_ERR_TREE for a malformed parent array; the others as above.
+ */
+int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
+                        const void *k_tree, const void *v_tree, const int32_t *parent,
+                        int n_tree, float scale, float *out, float *lse, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/*
+ * Tuning hook (not needed for correct results): overrides a launch-geometry choice until
+ * reset with value 0.  Names: "verify_splits", "partial_seg_keys".  Returns TS_OK, or
+ * TS_ERR_UNSUPPORTED for an unknown name or a value the kernels cannot run.  The same
+ * setting is seen by ts_workspace_bytes.  Not thread-safe against concurrent calls.
+ */
+int ts_tune_set(const char *name, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOKENSWIFT_H */
