@@ -1,0 +1,173 @@
+"""Benchmark of the decode-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
+
+One step = one pass of the whole path (chunk scores -> top-k -> partial-KV attention -> tree
+verification) over every layer's own cache of the workload; caches are resident in HBM before
+the timed region and each layer has its own, so every launch reads cold data.  Prints one
+JSON line; see the design doc for the definitions of the fields.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="index into the workload list (3 = MHA, 100K tokens)")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layer caches (0 = the config's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-loops", type=int, default=2, help="extra sweeps of the verify kernel alone for the roofline figure")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, layer_inputs, n_heads_sample):
+    """Time the fp64 oracle (as it stands, untuned) on the first n_heads_sample KV heads of one
+    layer, whole path, and scale to a full layer-step."""
+    import numpy as np
+    import oracle
+    import ts_synth as S
+
+    g = cfg.group
+    hs, qs = n_heads_sample, n_heads_sample * g
+    bits = lambda t: S.torch_bf16_to_bits(t)
+    q = bits(layer_inputs["q"][:qs])
+    k = bits(layer_inputs["k"][:hs])
+    v = bits(layer_inputs["v"][:hs])
+    q_tree = bits(layer_inputs["q_tree"][:, :qs])
+    k_tree = bits(layer_inputs["k_tree"][:, :hs])
+    v_tree = bits(layer_inputs["v_tree"][:, :hs])
+    t0 = time.perf_counter()
+    sc = oracle.chunk_scores(q, k, cfg.chunk, cfg.scale)
+    idx = oracle.topk_chunks(sc.astype(np.float32), cfg.n_sink, cfg.k)
+    oracle.partial_attn(q, k, v, idx, cfg.chunk, cfg.scale)
+    oracle.tree_verify(q_tree, k, v, k_tree, v_tree, layer_inputs["parent"], cfg.scale)
+    dt = time.perf_counter() - t0
+    return {"value": dt * 1e6 * (cfg.n_kv_heads / hs), "unit": "us/layer-step", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds_measured": round(dt, 2),
+            "sample": "fp64 oracle, whole path on the first %d of %d KV heads of one layer, scaled by %d/%d" % (
+                hs, cfg.n_kv_heads, cfg.n_kv_heads, hs)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (got --gpus %d); nothing here uses a second GPU" % args.gpus)
+    import torch
+    import paper_2502_18890_amd as ts
+    import ts_synth as S
+
+    ts.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = S.CONFIGS[args.config]
+    n_layers = args.layers or cfg.n_layers
+    layer_bytes = cfg.n_kv_heads * cfg.n_tokens * cfg.head_dim * 2 * 2
+    # small configs: replicate until the rotating working set is well beyond the on-die caches
+    while n_layers * layer_bytes < (2 << 30):
+        n_layers += cfg.n_layers
+
+    layers = [S.make_layer_torch(cfg, l, dev) for l in range(n_layers)]
+    hq, hkv, n, t = cfg.n_q_heads, cfg.n_kv_heads, cfg.n_tokens, cfg.n_tree
+    ws_v = torch.empty(ts.workspace_bytes(ts.OP_TREE_VERIFY, hq, hkv, n, t), dtype=torch.uint8, device=dev)
+    ws_p = torch.empty(ts.workspace_bytes(ts.OP_PARTIAL_ATTN, hq, hkv, n, 0, cfg.n_sel, cfg.chunk), dtype=torch.uint8, device=dev)
+    scores = torch.empty(hkv, cfg.n_chunks, dtype=torch.float32, device=dev)
+    idx = torch.empty(hkv, cfg.n_sel, dtype=torch.int32, device=dev)
+    out_p = torch.empty(hq, cfg.head_dim, dtype=torch.float32, device=dev)
+    out_v = torch.empty(t, hq, cfg.head_dim, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    def do_scores(x):
+        ts.chunk_scores(x["q"], x["k"], cfg.chunk, cfg.scale, out=scores)
+
+    def do_topk(x):
+        ts.topk_chunks(scores, cfg.n_sink, cfg.k, out=idx)
+
+    def do_partial(x):
+        ts.partial_kv_attn(x["q"], x["k"], x["v"], idx, cfg.chunk, cfg.scale, out=out_p, workspace=ws_p)
+
+    def do_verify(x):
+        ts.tree_verify_attn(x["q_tree"], x["k"], x["v"], x["k_tree"], x["v_tree"], x["parent"], cfg.scale,
+                            out=out_v, workspace=ws_v)
+
+    def step():
+        for x in layers:
+            do_scores(x)
+            do_topk(x)
+            do_partial(x)
+            do_verify(x)
+
+    def timed(fn, reps):
+        """ms per call of fn over reps calls, HIP events on the current stream."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    ms_per_step = timed(step, args.steps)
+    wall = time.perf_counter() - wall0
+
+    # per-function breakdown (each swept over all layers, same rotation)
+    def sweep(fn):
+        return lambda: [fn(x) for x in layers]
+    reps = max(2, args.steps // 4)
+    parts = {name: timed(sweep(fn), reps) * 1e3 / n_layers
+             for name, fn in (("scores", do_scores), ("topk", do_topk), ("partial", do_partial), ("verify", do_verify))}
+
+    # the dominant kernel alone (split kernel of the verification pass), for the roofline
+    ts.tune_set("verify_stage", 1)
+    try:
+        timed(sweep(do_verify), 1)
+        kern_us = timed(sweep(do_verify), max(1, args.kernel_loops)) * 1e3 / n_layers
+    finally:
+        ts.tune_set("verify_stage", 0)
+    alg_bytes = (hkv * n * cfg.head_dim * 2 * 2 + t * hkv * cfg.head_dim * 2 * 2 + t * hq * cfg.head_dim * 2
+                 + t * hq * cfg.head_dim * 4)
+    achieved = alg_bytes / (kern_us * 1e-6) / 1e9
+
+    us_per_layer_step = ms_per_step * 1e3 / n_layers
+    res = {
+        "metric": "us per layer-step: chunk scores + top-k + partial-KV attention + tree-verify attention over the full cache",
+        "value": round(us_per_layer_step, 3), "unit": "us/layer-step", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 inputs, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": "%s: %d q heads / %d kv heads, d=128, N=%d cached tokens, chunk %d, top-k %d+%d chunks, tree %d nodes, %d layer caches, batch 1" % (
+            cfg.name, hq, hkv, n, cfg.chunk, cfg.k, cfg.n_sink, t, n_layers), "config_index": args.config,
+            "layers": n_layers, "n_tokens": n},
+        "breakdown_us_per_layer": {k: round(v, 3) for k, v in parts.items()},
+        "verify_plus_partial_us_per_layer": round(parts["verify"] + parts["partial"], 3),
+        "verify_call_gbs": round(alg_bytes / (parts["verify"] * 1e-6) / 1e9, 1),
+        "wall_s_timed_region": round(wall, 3),
+        "roofline": {"kernel": "verify_kernel (split-K tree-verify attention)", "bound": "hbm",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": round(kern_us, 3)},
+    }
+    if not args.no_cpu_baseline:
+        n_heads_sample = max(1, min(hkv, 2 if n >= 60000 else hkv))
+        res["cpu_baseline"] = cpu_baseline(cfg, layers[0], n_heads_sample)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

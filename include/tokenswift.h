@@ -151,7 +151,9 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
 
 /*
  * Tuning hook (not needed for correct results): overrides a launch-geometry choice until
- * reset with value 0.  Names: "verify_splits", "partial_seg_keys".  Returns TS_OK, or
+ * reset with value 0.  Names: "verify_splits" (number of cache splits per KV head);
+ * "verify_stage" (1: ts_tree_verify_attn enqueues only its split kernel, 2: only its merge
+ * kernel -- for timing one kernel alone; outputs are then not meaningful).  Returns TS_OK, or
  * TS_ERR_UNSUPPORTED for an unknown name or a value the kernels cannot run.  The same
  * setting is seen by ts_workspace_bytes.  Not thread-safe against concurrent calls.
  */

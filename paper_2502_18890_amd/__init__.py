@@ -1,0 +1,13 @@
+"""MI355X-native decode-attention hot path of TokenSwift (arXiv 2502.18890).
+
+Thin Python front end of ``libtokenswift_hip.so`` (C ABI in ``include/tokenswift.h``): chunk
+importance scores, top-k chunk selection, partial-KV attention and tree-verification attention
+as hand-written gfx950 kernels.  PyTorch is used only for device memory and streams.
+"""
+from .binding import (TokenSwiftError, chunk_scores, lib_path, load_library, partial_kv_attn,
+                      topk_chunks, tree_verify_attn, tune_set, version, workspace_bytes,
+                      OP_PARTIAL_ATTN, OP_TREE_VERIFY)
+
+__all__ = ["TokenSwiftError", "chunk_scores", "lib_path", "load_library", "partial_kv_attn",
+           "topk_chunks", "tree_verify_attn", "tune_set", "version", "workspace_bytes",
+           "OP_PARTIAL_ATTN", "OP_TREE_VERIFY"]

@@ -1,0 +1,57 @@
+// Merge of split-K attention partials: for each query row, partial i carries the maximum
+// logit m_i (exp2 domain), l_i = sum exp2(logit - m_i) and O_i = sum exp2(logit - m_i) * v over
+// its own keys.  Softmax attention over the union of the key sets is
+//   m* = max m_i,  l* = sum l_i 2^(m_i - m*),  out = sum O_i 2^(m_i - m*) / l*,
+// and the natural-log sum of exponentials is (m* + log2 l*) ln 2.
+// One wavefront per row, two output columns per lane.
+#include "ts_device.hpp"
+#include "ts_internal.hpp"
+
+namespace ts {
+
+namespace {
+
+__global__ void __launch_bounds__(256) combine_kernel(const CombineParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int row = blockIdx.x * 4 + wave;
+    const int h = blockIdx.y;
+    if (row >= p.n_rows) return;   // whole wavefront leaves together
+
+    const int64_t pitch = p.row_pitch;
+    const int64_t first = (int64_t)h * p.n_part * pitch + row;   // partial pp at first + pp*pitch
+
+    float mstar = kNegBig;
+    for (int pp = lane; pp < p.n_part; pp += 64)
+        mstar = fmaxf(mstar, p.ws_ml[(first + (int64_t)pp * pitch) * 2]);
+    mstar = wave_max(mstar);
+
+    f32x2 acc = {0.f, 0.f};
+    float lstar = 0.f;
+    for (int pp = 0; pp < p.n_part; ++pp) {
+        const int64_t at = first + (int64_t)pp * pitch;
+        const f32x2 ml = *reinterpret_cast<const f32x2 *>(p.ws_ml + at * 2);
+        const float w = fast_exp2(ml[0] - mstar);
+        const f32x2 o = *reinterpret_cast<const f32x2 *>(p.ws_o + at * kHeadDim + lane * 2);
+        lstar += w * ml[1];
+        acc += o * w;
+    }
+    const int node = row / p.group, jj = row % p.group;
+    const int64_t orow = (int64_t)node * p.n_q_heads + h * p.group + jj;
+    const float inv = 1.0f / lstar;
+    f32x2 res = {acc[0] * inv, acc[1] * inv};
+    *reinterpret_cast<f32x2 *>(p.out + orow * kHeadDim + lane * 2) = res;
+    if (p.lse != nullptr && lane == 0) p.lse[orow] = (mstar + fast_log2(lstar)) * kLn2;
+}
+
+}  // namespace
+
+hipError_t launch_combine(const CombineParams &p, hipStream_t stream)
+{
+    dim3 grid((p.n_rows + 3) / 4, p.n_kv_heads);
+    hipLaunchKernelGGL(combine_kernel, grid, dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace ts

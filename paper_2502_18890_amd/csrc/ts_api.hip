@@ -1,0 +1,312 @@
+// C ABI of the library: argument validation, launch-geometry choice, workspace carve-up.
+// All validation happens on the host before anything is enqueued.
+#include <string.h>
+
+#include "../../include/tokenswift.h"
+#include "ts_internal.hpp"
+
+namespace {
+
+constexpr int kNumCUs = 256;   // MI355X
+
+struct Tuning {
+    int verify_splits = 0;     // 0 = heuristic
+    int verify_stage = 0;      // 0 = both kernels, 1 = split kernel only, 2 = merge kernel only
+} g_tune;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int check_view(const ts_kv_view *kv, bool need_v, bool allow_empty)
+{
+    if (!kv) return TS_ERR_NULL;
+    if (kv->head_dim != TS_HEAD_DIM) return TS_ERR_UNSUPPORTED;
+    if (kv->n_kv_heads < 1) return TS_ERR_SHAPE;
+    if (kv->n_tokens < 0 || (kv->n_tokens == 0 && !allow_empty)) return TS_ERR_SHAPE;
+    if (kv->n_tokens == 0) return TS_OK;
+    if (!kv->k || (need_v && !kv->v)) return TS_ERR_NULL;
+    if (kv->stride_token < TS_HEAD_DIM || kv->stride_head < 0) return TS_ERR_SHAPE;
+    if ((kv->stride_token % 8) != 0 || (kv->stride_head % 8) != 0) return TS_ERR_ALIGN;
+    if (!aligned16(kv->k) || (need_v && !aligned16(kv->v))) return TS_ERR_ALIGN;
+    return TS_OK;
+}
+
+int check_heads(int n_q_heads, int n_kv_heads, int *group)
+{
+    if (n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads != 0) return TS_ERR_SHAPE;
+    *group = n_q_heads / n_kv_heads;
+    if (*group > TS_MAX_GROUP) return TS_ERR_UNSUPPORTED;
+    return TS_OK;
+}
+
+// ---- geometry of the verification pass ------------------------------------------------------
+struct VerifyPlan {
+    int n_rows, n_rows_pad, n_split;
+    int64_t split_len;
+    size_t ml_offset, bytes;
+};
+
+// Splits of the cache: enough workgroups to keep every CU's latency-hiding slots full,
+// but few enough that the fp32 partials (520 B per row and split) stay a small fraction of
+// the K/V bytes (512 B per cached token).
+bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, VerifyPlan *pl)
+{
+    const int group = n_q_heads / n_kv_heads;
+    pl->n_rows = group * n_tree;
+    pl->n_rows_pad = ts::verify_rows_capacity(pl->n_rows);
+    if (pl->n_rows_pad == 0) return false;
+    int n_split = 0;
+    int64_t split_len = 32;
+    if (n_tokens > 0) {
+        // resident workgroups per CU of the kernel shape that covers n_rows_pad rows
+        const int cap = pl->n_rows_pad;
+        const int wg_per_cu = cap <= 16 ? 8 : (cap <= 64 ? 4 : (cap <= 128 ? 2 : 1));
+        int64_t want = ((int64_t)kNumCUs * wg_per_cu + n_kv_heads - 1) / n_kv_heads;
+        const int64_t cap_traffic = (n_tokens * 512 / 8) / ((int64_t)pl->n_rows_pad * 520) + 1;  // partials <= 1/8 of K/V
+        if (want > cap_traffic) want = cap_traffic;
+        if (g_tune.verify_splits > 0) want = g_tune.verify_splits;
+        const int64_t max_split = (n_tokens + 31) / 32;
+        if (want > max_split) want = max_split;
+        if (want < 1) want = 1;
+        split_len = ((n_tokens + want - 1) / want + 31) / 32 * 32;
+        n_split = (int)((n_tokens + split_len - 1) / split_len);
+    }
+    pl->n_split = n_split;
+    pl->split_len = split_len;
+    const size_t rows_total = (size_t)n_kv_heads * (n_split + 1) * pl->n_rows_pad;
+    pl->ml_offset = round_up(rows_total * TS_HEAD_DIM * sizeof(float), 256);
+    pl->bytes = pl->ml_offset + round_up(rows_total * 2 * sizeof(float), 256);
+    return true;
+}
+
+struct PartialPlan {
+    int segs_per_chunk, n_part;
+    size_t ml_offset, bytes;
+};
+
+void plan_partial(int n_q_heads, int n_kv_heads, int n_sel, int chunk_size, PartialPlan *pl)
+{
+    const int group = n_q_heads / n_kv_heads;
+    pl->segs_per_chunk = chunk_size / 16;
+    pl->n_part = n_sel * pl->segs_per_chunk;
+    const size_t rows_total = (size_t)n_kv_heads * pl->n_part * group;
+    pl->ml_offset = round_up(rows_total * TS_HEAD_DIM * sizeof(float), 256);
+    pl->bytes = pl->ml_offset + round_up(rows_total * 2 * sizeof(float), 256);
+}
+
+bool partial_chunk_ok(int chunk_size) { return chunk_size >= 16 && chunk_size <= 1024 && chunk_size % 16 == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char *ts_strerror(int status)
+{
+    switch (status) {
+        case TS_OK: return "ok";
+        case TS_ERR_NULL: return "a required pointer is NULL";
+        case TS_ERR_SHAPE: return "sizes are inconsistent or out of range";
+        case TS_ERR_UNSUPPORTED: return "shape not supported by the kernels";
+        case TS_ERR_TREE: return "parent array is not a forest in topological order";
+        case TS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case TS_ERR_HIP: return "HIP runtime error";
+        case TS_ERR_ALIGN: return "pointer or stride breaks 16-byte row alignment";
+        default: return "unknown status";
+    }
+}
+
+int ts_version(void) { return 100; }
+
+int ts_tune_set(const char *name, int value)
+{
+    if (!name || value < 0) return TS_ERR_UNSUPPORTED;
+    if (strcmp(name, "verify_splits") == 0) {
+        g_tune.verify_splits = value;
+        return TS_OK;
+    }
+    if (strcmp(name, "verify_stage") == 0) {
+        if (value > 2) return TS_ERR_UNSUPPORTED;
+        g_tune.verify_stage = value;
+        return TS_OK;
+    }
+    return TS_ERR_UNSUPPORTED;
+}
+
+size_t ts_workspace_bytes(int op, int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree,
+                          int n_sel, int chunk_size)
+{
+    int group = 0;
+    if (check_heads(n_q_heads, n_kv_heads, &group) != TS_OK) return 0;
+    if (op == TS_OP_TREE_VERIFY) {
+        if (n_tree < 1 || n_tree > TS_MAX_TREE || n_tokens < 0) return 0;
+        VerifyPlan pl;
+        if (!plan_verify(n_q_heads, n_kv_heads, n_tokens, n_tree, &pl)) return 0;
+        return pl.bytes;
+    }
+    if (op == TS_OP_PARTIAL_ATTN) {
+        if (n_sel < 1 || !partial_chunk_ok(chunk_size)) return 0;
+        PartialPlan pl;
+        plan_partial(n_q_heads, n_kv_heads, n_sel, chunk_size, &pl);
+        return pl.bytes;
+    }
+    return 0;
+}
+
+int ts_chunk_scores(const ts_kv_view *kv, const void *q, int n_q_heads, int chunk_size,
+                    float scale, float *scores, void *stream)
+{
+    int rc = check_view(kv, false, false);
+    if (rc != TS_OK) return rc;
+    if (!q || !scores) return TS_ERR_NULL;
+    int group = 0;
+    if ((rc = check_heads(n_q_heads, kv->n_kv_heads, &group)) != TS_OK) return rc;
+    if (chunk_size < 1 || chunk_size > 1024) return TS_ERR_UNSUPPORTED;
+    if (!aligned16(q)) return TS_ERR_ALIGN;
+    ts::ScoresParams p;
+    p.q = static_cast<const uint16_t *>(q);
+    p.k = static_cast<const uint16_t *>(kv->k);
+    p.scores = scores;
+    p.stride_head = kv->stride_head;
+    p.stride_token = kv->stride_token;
+    p.n_tokens = kv->n_tokens;
+    p.n_chunks = (kv->n_tokens + chunk_size - 1) / chunk_size;
+    if ((p.n_chunks + 3) / 4 > 0x7fffffffLL) return TS_ERR_UNSUPPORTED;
+    p.n_q_heads = n_q_heads;
+    p.n_kv_heads = kv->n_kv_heads;
+    p.group = group;
+    p.chunk_size = chunk_size;
+    p.scale = scale;
+    return ts::launch_scores(p, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int ts_topk_chunks(const float *scores, int n_kv_heads, int n_chunks, int n_sink_chunks, int k,
+                   int32_t *idx_out, void *stream)
+{
+    if (!scores || !idx_out) return TS_ERR_NULL;
+    if (n_kv_heads < 1 || n_chunks < 1 || n_sink_chunks < 0 || k < 0) return TS_ERR_SHAPE;
+    if ((int64_t)n_sink_chunks + k > n_chunks || n_sink_chunks + k < 1) return TS_ERR_SHAPE;
+    if (n_chunks > TS_MAX_CHUNKS) return TS_ERR_UNSUPPORTED;
+    ts::TopkParams p;
+    p.scores = scores;
+    p.idx_out = idx_out;
+    p.n_kv_heads = n_kv_heads;
+    p.n_chunks = n_chunks;
+    p.n_sink = n_sink_chunks;
+    p.k = k;
+    return ts::launch_topk(p, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
+                       const int32_t *chunk_idx, int n_sel, int chunk_size, float scale,
+                       float *out, float *lse, void *workspace, size_t workspace_bytes,
+                       void *stream)
+{
+    int rc = check_view(kv, true, false);
+    if (rc != TS_OK) return rc;
+    if (!q || !chunk_idx || !out) return TS_ERR_NULL;
+    int group = 0;
+    if ((rc = check_heads(n_q_heads, kv->n_kv_heads, &group)) != TS_OK) return rc;
+    if (n_sel < 1) return TS_ERR_SHAPE;
+    if (!partial_chunk_ok(chunk_size)) return TS_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(out)) return TS_ERR_ALIGN;
+    PartialPlan pl;
+    plan_partial(n_q_heads, kv->n_kv_heads, n_sel, chunk_size, &pl);
+    if (!workspace || workspace_bytes < pl.bytes || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return TS_ERR_WORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ts::PartialParams p;
+    p.q = static_cast<const uint16_t *>(q);
+    p.k = static_cast<const uint16_t *>(kv->k);
+    p.v = static_cast<const uint16_t *>(kv->v);
+    p.chunk_idx = chunk_idx;
+    p.ws_o = reinterpret_cast<float *>(workspace);
+    p.ws_ml = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.ml_offset);
+    p.stride_head = kv->stride_head;
+    p.stride_token = kv->stride_token;
+    p.n_tokens = kv->n_tokens;
+    p.n_q_heads = n_q_heads;
+    p.n_kv_heads = kv->n_kv_heads;
+    p.group = group;
+    p.n_sel = n_sel;
+    p.chunk_size = chunk_size;
+    p.segs_per_chunk = pl.segs_per_chunk;
+    p.n_part = pl.n_part;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    if (ts::launch_partial(p, st) != hipSuccess) return TS_ERR_HIP;
+
+    ts::CombineParams c;
+    c.ws_o = p.ws_o;
+    c.ws_ml = p.ws_ml;
+    c.out = out;
+    c.lse = lse;
+    c.n_kv_heads = kv->n_kv_heads;
+    c.n_q_heads = n_q_heads;
+    c.group = group;
+    c.n_part = pl.n_part;
+    c.n_rows = group;
+    c.row_pitch = group;
+    return ts::launch_combine(c, st) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
+                        const void *k_tree, const void *v_tree, const int32_t *parent,
+                        int n_tree, float scale, float *out, float *lse, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    int rc = check_view(kv, true, true);
+    if (rc != TS_OK) return rc;
+    if (!q_tree || !k_tree || !v_tree || !parent || !out) return TS_ERR_NULL;
+    int group = 0;
+    if ((rc = check_heads(n_q_heads, kv->n_kv_heads, &group)) != TS_OK) return rc;
+    if (n_tree < 1) return TS_ERR_SHAPE;
+    if (n_tree > TS_MAX_TREE) return TS_ERR_UNSUPPORTED;
+    for (int i = 0; i < n_tree; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return TS_ERR_TREE;
+    if (!aligned16(q_tree) || !aligned16(k_tree) || !aligned16(v_tree) || !aligned16(out)) return TS_ERR_ALIGN;
+    VerifyPlan pl;
+    if (!plan_verify(n_q_heads, kv->n_kv_heads, kv->n_tokens, n_tree, &pl)) return TS_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < pl.bytes || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return TS_ERR_WORKSPACE;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    ts::VerifyParams p;
+    p.q = static_cast<const uint16_t *>(q_tree);
+    p.k = static_cast<const uint16_t *>(kv->k);
+    p.v = static_cast<const uint16_t *>(kv->v);
+    p.k_tree = static_cast<const uint16_t *>(k_tree);
+    p.v_tree = static_cast<const uint16_t *>(v_tree);
+    p.ws_o = reinterpret_cast<float *>(workspace);
+    p.ws_ml = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.ml_offset);
+    p.stride_head = kv->stride_head;
+    p.stride_token = kv->stride_token;
+    p.n_tokens = kv->n_tokens;
+    p.split_len = pl.split_len;
+    p.n_split = pl.n_split;
+    p.n_q_heads = n_q_heads;
+    p.n_kv_heads = kv->n_kv_heads;
+    p.group = group;
+    p.n_tree = n_tree;
+    p.n_rows = pl.n_rows;
+    p.n_rows_pad = pl.n_rows_pad;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    // ancestor-or-self bit masks (App. E: a node attends only to its predecessors)
+    for (int i = 0; i < 64; ++i) p.anc[i] = 0;
+    for (int i = 0; i < n_tree; ++i)
+        p.anc[i] = (1ull << i) | (parent[i] >= 0 ? p.anc[parent[i]] : 0ull);
+    if (g_tune.verify_stage != 2 && ts::launch_verify(p, st) != hipSuccess) return TS_ERR_HIP;
+    if (g_tune.verify_stage == 1) return TS_OK;
+
+    ts::CombineParams c;
+    c.ws_o = p.ws_o;
+    c.ws_ml = p.ws_ml;
+    c.out = out;
+    c.lse = lse;
+    c.n_kv_heads = kv->n_kv_heads;
+    c.n_q_heads = n_q_heads;
+    c.group = group;
+    c.n_part = pl.n_split + 1;
+    c.n_rows = pl.n_rows;
+    c.row_pitch = pl.n_rows_pad;
+    return ts::launch_combine(c, st) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+}  // extern "C"

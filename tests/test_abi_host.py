@@ -1,0 +1,133 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function
+the header declares, sizes its workspace sanely, and rejects bad arguments before anything
+could be launched (no compute call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "tokenswift.h")
+
+TS_OK, TS_ERR_NULL, TS_ERR_SHAPE, TS_ERR_UNSUPPORTED = 0, -1, -2, -3
+TS_ERR_TREE, TS_ERR_WORKSPACE, TS_ERR_HIP, TS_ERR_ALIGN = -4, -5, -6, -7
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2502_18890_amd import binding
+    return binding.load_library()
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2502_18890_amd import binding as b
+    return b
+
+
+def test_library_exports_every_declared_function(lib):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(ts_[a-z_]+)\s*\(", text)))
+    assert names == ["ts_chunk_scores", "ts_partial_kv_attn", "ts_strerror", "ts_topk_chunks",
+                     "ts_tree_verify_attn", "ts_tune_set", "ts_version", "ts_workspace_bytes"]
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.ts_version() >= 100
+
+
+def test_strerror_covers_all_codes(lib):
+    seen = set()
+    for code in range(0, -8, -1):
+        s = lib.ts_strerror(code).decode()
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 8
+    assert lib.ts_strerror(-99).decode() == "unknown status"
+
+
+def test_workspace_bytes(binding):
+    wb = binding.workspace_bytes
+    V, P = binding.OP_TREE_VERIFY, binding.OP_PARTIAL_ATTN
+    assert wb(V, 32, 32, 100000, 32) > 0
+    assert wb(V, 32, 32, 0, 32) > 0                       # empty cache: tree partial only
+    assert wb(V, 32, 32, 100000, 0) == 0                  # no tree
+    assert wb(V, 32, 32, 100000, 65) == 0                 # tree too large
+    assert wb(V, 30, 8, 1000, 8) == 0                     # heads do not divide
+    assert wb(V, 72, 8, 1000, 8) == 0                     # group 9 > 8
+    assert wb(P, 32, 8, 65536, 0, 65, 64) >= 8 * 65 * 4 * 4 * (128 + 2) * 4   # one partial per 16-token segment
+    assert wb(P, 32, 8, 65536, 0, 0, 64) == 0             # empty selection
+    assert wb(P, 32, 8, 65536, 0, 65, 24) == 0            # chunk not a multiple of 16
+    assert wb(99, 32, 8, 65536, 8, 65, 64) == 0
+    # the partials must stay a small fraction of the K/V bytes at the benchmark shapes
+    for hq, hkv, n, t in [(32, 8, 65536, 32), (32, 32, 100000, 32), (40, 8, 102400, 64)]:
+        assert wb(V, hq, hkv, n, t) < 0.3 * hkv * n * 512
+
+
+def _view(binding, k=0x1000, v=0x2000, n=100, hkv=2, d=128, sh=12800, st=128):
+    return binding._KvView(k, v, n, hkv, d, sh, st)
+
+
+def test_scores_and_topk_reject_bad_arguments(lib, binding):
+    q, out = 0x3000, 0x4000
+    cs = lambda view, q_=q, hq=4, chunk=64, out_=out: lib.ts_chunk_scores(
+        ctypes.byref(view) if view is not None else None, q_, hq, chunk, 1.0, out_, None)
+    assert cs(None) == TS_ERR_NULL
+    assert cs(_view(binding), q_=None) == TS_ERR_NULL
+    assert cs(_view(binding), out_=None) == TS_ERR_NULL
+    assert cs(_view(binding, k=None)) == TS_ERR_NULL
+    assert cs(_view(binding, d=64)) == TS_ERR_UNSUPPORTED
+    assert cs(_view(binding, n=0)) == TS_ERR_SHAPE
+    assert cs(_view(binding), hq=3) == TS_ERR_SHAPE
+    assert cs(_view(binding), hq=18) == TS_ERR_UNSUPPORTED      # group 9
+    assert cs(_view(binding), chunk=0) == TS_ERR_UNSUPPORTED
+    assert cs(_view(binding), chunk=2048) == TS_ERR_UNSUPPORTED
+    assert cs(_view(binding, k=0x1004)) == TS_ERR_ALIGN
+    assert cs(_view(binding, st=132)) == TS_ERR_ALIGN
+    assert cs(_view(binding, st=64)) == TS_ERR_SHAPE
+    tk = lambda n_chunks=10, sink=1, k=3, s=0x1000, o=0x2000: lib.ts_topk_chunks(s, 2, n_chunks, sink, k, o, None)
+    assert tk(s=None) == TS_ERR_NULL and tk(o=None) == TS_ERR_NULL
+    assert tk(sink=8, k=3) == TS_ERR_SHAPE
+    assert tk(sink=0, k=0) == TS_ERR_SHAPE
+    assert tk(k=-1) == TS_ERR_SHAPE and tk(sink=-1) == TS_ERR_SHAPE and tk(n_chunks=0) == TS_ERR_SHAPE
+    assert tk(n_chunks=8193) == TS_ERR_UNSUPPORTED
+
+
+def test_attention_calls_reject_bad_arguments(lib, binding):
+    q, idx, out, ws = 0x3000, 0x5000, 0x4000, 0x10000
+    big = 1 << 30
+    pa = lambda view=None, hq=4, n_sel=3, chunk=64, ws_=ws, wsb=big, q_=q, idx_=idx, out_=out: lib.ts_partial_kv_attn(
+        ctypes.byref(view if view is not None else _view(binding)), q_, hq, idx_, n_sel, chunk, 1.0, out_, None,
+        ws_, wsb, None)
+    assert pa(idx_=None) == TS_ERR_NULL and pa(out_=None) == TS_ERR_NULL and pa(q_=None) == TS_ERR_NULL
+    assert pa(view=_view(binding, v=None)) == TS_ERR_NULL
+    assert pa(n_sel=0) == TS_ERR_SHAPE
+    assert pa(chunk=24) == TS_ERR_UNSUPPORTED and pa(chunk=8) == TS_ERR_UNSUPPORTED
+    assert pa(ws_=None) == TS_ERR_WORKSPACE and pa(wsb=16) == TS_ERR_WORKSPACE
+    assert pa(ws_=ws + 16) == TS_ERR_WORKSPACE                  # not 256-byte aligned
+    assert pa(out_=out + 4) == TS_ERR_ALIGN
+
+    def tv(parent, view=None, hq=4, ws_=ws, wsb=big, kt=0x6000, out_=out):
+        par = (ctypes.c_int32 * len(parent))(*parent) if parent is not None else None
+        return lib.ts_tree_verify_attn(ctypes.byref(view if view is not None else _view(binding)), q, hq, kt, 0x7000,
+                                       par, len(parent) if parent is not None else 4, 1.0, out_, None, ws_, wsb, None)
+    assert tv(None) == TS_ERR_NULL
+    assert tv([-1, 0], kt=None) == TS_ERR_NULL
+    assert tv([0, 0]) == TS_ERR_TREE            # a node cannot be its own parent
+    assert tv([-1, 1]) == TS_ERR_TREE           # parent must come earlier
+    assert tv([-1, 0, 3]) == TS_ERR_TREE
+    assert tv([-2, 0]) == TS_ERR_TREE
+    assert tv([]) == TS_ERR_SHAPE
+    assert tv([-1] * 65) == TS_ERR_UNSUPPORTED
+    assert tv([-1, 0], hq=3) == TS_ERR_SHAPE
+    assert tv([-1, 0], ws_=None) == TS_ERR_WORKSPACE and tv([-1, 0], wsb=100) == TS_ERR_WORKSPACE
+    assert tv([-1, 0], view=_view(binding, d=96)) == TS_ERR_UNSUPPORTED
+
+
+def test_tune_set(lib):
+    assert lib.ts_tune_set(b"verify_splits", 7) == TS_OK
+    assert lib.ts_tune_set(b"verify_splits", 0) == TS_OK
+    assert lib.ts_tune_set(b"no_such_knob", 1) == TS_ERR_UNSUPPORTED
+    assert lib.ts_tune_set(b"verify_splits", -1) == TS_ERR_UNSUPPORTED
+    assert lib.ts_tune_set(None, 1) == TS_ERR_UNSUPPORTED

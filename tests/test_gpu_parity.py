@@ -1,0 +1,247 @@
+"""GPU parity: every entry point of the C ABI against the fp64 oracle, element by element, on
+the same seeded inputs (sizes that span several tiles and ragged tails, plus edge cases)."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import ts_synth as S
+from gpu_util import assert_close, dev
+from helpers import rand_bits
+
+pytestmark = pytest.mark.gpu
+
+D = 128
+SCALE = 1.0 / math.sqrt(D)
+
+
+@pytest.fixture(scope="module")
+def ts():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2502_18890_amd as lib
+    lib.load_library()
+    return lib
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _case(seed, hq, hkv, n, t, vscale=1.0, kscale=1.0):
+    rng = np.random.default_rng(seed)
+    return dict(q=rand_bits(rng, hq, D), q_tree=rand_bits(rng, t, hq, D), k_tree=rand_bits(rng, t, hkv, D, scale=kscale),
+                v_tree=rand_bits(rng, t, hkv, D, scale=vscale), k=rand_bits(rng, hkv, max(n, 1), D, scale=kscale)[:, :n],
+                v=rand_bits(rng, hkv, max(n, 1), D, scale=vscale)[:, :n], rng=rng)
+
+
+def _random_parent(rng, t):
+    p = np.full(t, -1, dtype=np.int32)
+    for i in range(1, t):
+        p[i] = rng.integers(-1, i)     # -1 allowed: forests with several roots
+    return p
+
+
+# ------------------------------------------------------------------------------------------
+# chunk scores
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("hq,hkv,n,chunk", [(4, 1, 4096, 64), (12, 2, 16384, 64), (32, 8, 1000, 64),
+                                            (32, 32, 1567, 64), (40, 8, 777, 64), (6, 1, 300, 16),
+                                            (8, 1, 257, 128), (4, 2, 130, 1), (7, 7, 5, 64), (16, 2, 3000, 1000),
+                                            (3, 1, 100, 48)])
+def test_chunk_scores(ts, hq, hkv, n, chunk):
+    c = _case(1, hq, hkv, n, 1)
+    got = ts.chunk_scores(dev(c["q"]), dev(c["k"]), chunk, SCALE)
+    ref = oracle.chunk_scores(c["q"], c["k"], chunk, SCALE)
+    assert_close(_np(got), ref, "chunk_scores")
+
+
+def test_chunk_scores_token_major_layout(ts):
+    """K stored [N, Hkv, d] and passed as a strided [Hkv, N, d] view."""
+    rng = np.random.default_rng(2)
+    hq, hkv, n = 8, 4, 1234
+    q = rand_bits(rng, hq, D)
+    k_tm = rand_bits(rng, n, hkv, D)
+    got = ts.chunk_scores(dev(q), dev(k_tm).transpose(0, 1), 64, SCALE)
+    ref = oracle.chunk_scores(q, k_tm.transpose(1, 0, 2), 64, SCALE)
+    assert_close(_np(got), ref, "chunk_scores token-major")
+
+
+# ------------------------------------------------------------------------------------------
+# top-k: bit-exact from the same fp32 score vector
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("hkv,n_chunks,n_sink,k", [(1, 64, 1, 8), (2, 256, 1, 64), (8, 1024, 1, 64), (32, 1563, 1, 64),
+                                                   (8, 1600, 1, 128), (3, 1, 1, 0), (3, 1, 0, 1), (2, 2, 0, 2),
+                                                   (2, 17, 3, 14), (1, 8192, 2, 512), (4, 100, 0, 100), (2, 33, 33, 0)])
+def test_topk_matches_oracle_bit_exact(ts, hkv, n_chunks, n_sink, k):
+    import torch
+    rng = np.random.default_rng(3)
+    s = rng.standard_normal((hkv, n_chunks)).astype(np.float32)
+    s[:, ::5] = np.round(s[:, ::5] * 2) / 2            # many exact ties
+    got = ts.topk_chunks(torch.from_numpy(s).cuda(), n_sink, k)
+    ref = oracle.topk_chunks(s, n_sink, k)
+    np.testing.assert_array_equal(_np(got), ref)
+
+
+def test_topk_special_values(ts):
+    import torch
+    s = np.array([[5.0, 1.0, 1.0, -0.0, 0.0, np.nan, 1.0, np.nan, -np.inf, np.inf, -1e-45, 1e-45, 3.4e38, -3.4e38]],
+                 dtype=np.float32)
+    for n_sink in (0, 1, 2):
+        k = s.shape[1] - n_sink
+        got = ts.topk_chunks(torch.from_numpy(s).cuda(), n_sink, k)
+        np.testing.assert_array_equal(_np(got), oracle.topk_chunks(s, n_sink, k))
+    s = np.full((2, 70), 0.25, dtype=np.float32)
+    np.testing.assert_array_equal(_np(ts.topk_chunks(torch.from_numpy(s).cuda(), 1, 40)), oracle.topk_chunks(s, 1, 40))
+
+
+def test_scores_then_topk_pipeline(ts):
+    """Scores from the GPU feed both selections: indices must agree exactly; and with the planted
+    chunks of the tiny config the oracle's own fp64 scores select the same set."""
+    cfg = S.CONFIGS[0]
+    x = S.make_layer(cfg, 0)
+    sc = ts.chunk_scores(dev(x["q"]), dev(x["k"]), cfg.chunk, cfg.scale)
+    idx = _np(ts.topk_chunks(sc, cfg.n_sink, cfg.k))
+    np.testing.assert_array_equal(idx, oracle.topk_chunks(_np(sc), cfg.n_sink, cfg.k))
+    ref_idx = oracle.topk_chunks(oracle.chunk_scores(x["q"], x["k"], cfg.chunk, cfg.scale), cfg.n_sink, cfg.k)
+    assert set(idx[0].tolist()) == set(ref_idx[0].tolist())
+
+
+# ------------------------------------------------------------------------------------------
+# partial-KV attention
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("ci", [0, 1])
+def test_partial_attn_configs(ts, ci):
+    cfg = S.CONFIGS[ci]
+    x = S.make_layer(cfg, 0)
+    sc = oracle.chunk_scores(x["q"], x["k"], cfg.chunk, cfg.scale)
+    idx = oracle.topk_chunks(sc, cfg.n_sink, cfg.k)
+    import torch
+    out, lse = ts.partial_kv_attn(dev(x["q"]), dev(x["k"]), dev(x["v"]), torch.from_numpy(idx).cuda(), cfg.chunk,
+                                  cfg.scale, want_lse=True)
+    ref, rlse = oracle.partial_attn(x["q"], x["k"], x["v"], idx, cfg.chunk, cfg.scale)
+    assert_close(_np(out), ref, "partial out")
+    assert_close(_np(lse), rlse, "partial lse")
+
+
+@pytest.mark.parametrize("hq,hkv,n,chunk,sel", [
+    (4, 1, 300, 64, [[4, 0, 2]]),                 # last chunk has 44 tokens
+    (8, 8, 65, 64, [[1, 0]] * 8),                 # last chunk has 1 token
+    (5, 1, 1, 64, [[0]]),                         # single key
+    (6, 1, 17, 16, [[1, 0]]),                     # chunk 16, 1-token tail
+    (16, 2, 1000, 128, [[7, 3, 0], [0, 1, 2]]),   # chunk 128, 104-token tail
+    (8, 1, 200, 32, [[6, 6, 1]]),                 # a chunk listed twice counts twice
+    (2, 2, 4096, 64, [list(range(64))] * 2),      # every chunk: full attention
+    (3, 3, 640, 64, [[9, 8, 7, 6, 5, 4, 3, 2, 1, 0]] * 3),
+])
+def test_partial_attn_edges(ts, hq, hkv, n, chunk, sel):
+    import torch
+    c = _case(5, hq, hkv, n, 1, vscale=2.0)
+    idx = np.asarray(sel, dtype=np.int32)
+    out, lse = ts.partial_kv_attn(dev(c["q"]), dev(c["k"]), dev(c["v"]), torch.from_numpy(idx).cuda(), chunk, SCALE,
+                                  want_lse=True)
+    ref, rlse = oracle.partial_attn(c["q"], c["k"], c["v"], idx, chunk, SCALE)
+    assert_close(_np(out), ref, "partial out")
+    assert_close(_np(lse), rlse, "partial lse")
+
+
+# ------------------------------------------------------------------------------------------
+# tree verification attention
+# ------------------------------------------------------------------------------------------
+def _verify_both(ts, c, parent, scale=SCALE, layout="head"):
+    n = c["k"].shape[1]
+    if n == 0:
+        kd = vd = None
+    elif layout == "head":
+        kd, vd = dev(c["k"]), dev(c["v"])
+    else:   # token-major storage, strided view
+        kd = dev(np.ascontiguousarray(c["k"].transpose(1, 0, 2))).transpose(0, 1)
+        vd = dev(np.ascontiguousarray(c["v"].transpose(1, 0, 2))).transpose(0, 1)
+    out, lse = ts.tree_verify_attn(dev(c["q_tree"]), kd, vd, dev(c["k_tree"]), dev(c["v_tree"]), parent, scale,
+                                   want_lse=True)
+    ref, rlse = oracle.tree_verify(c["q_tree"], c["k"] if n else None, c["v"] if n else None, c["k_tree"],
+                                   c["v_tree"], parent, scale)
+    return _np(out), _np(lse), ref, rlse
+
+
+@pytest.mark.parametrize("ci", [0, 1])
+def test_verify_configs(ts, ci):
+    cfg = S.CONFIGS[ci]
+    x = S.make_layer(cfg, 0)
+    out, lse, ref, rlse = _verify_both(ts, x, x["parent"], cfg.scale)
+    assert_close(out, ref, "verify out")
+    assert_close(lse, rlse, "verify lse")
+
+
+@pytest.mark.parametrize("hq,hkv,n,t", [
+    (4, 1, 0, 8), (4, 1, 1, 1), (4, 4, 31, 5), (8, 2, 32, 16), (8, 2, 33, 16), (6, 1, 63, 7), (5, 1, 64, 13),
+    (12, 2, 65, 16), (32, 8, 4096 + 17, 32), (32, 32, 1000, 32), (40, 8, 2100, 64), (6, 1, 500, 64),
+    (8, 1, 300, 64), (8, 1, 700, 33), (16, 2, 257, 20), (7, 1, 129, 3), (2, 2, 97, 64), (3, 3, 5000, 2),
+])
+def test_verify_shapes(ts, hq, hkv, n, t):
+    c = _case(7, hq, hkv, n, t)
+    parent = _random_parent(c["rng"], t)
+    out, lse, ref, rlse = _verify_both(ts, c, parent)
+    assert_close(out, ref, "verify out")
+    assert_close(lse, rlse, "verify lse")
+
+
+@pytest.mark.parametrize("kind", ["chain", "star", "fixed"])
+def test_verify_tree_kinds(ts, kind):
+    c = _case(8, 8, 2, 200, 8)
+    parent = S.tree_parents(S.CONFIGS[0], 0, 8, kind)
+    out, lse, ref, rlse = _verify_both(ts, c, parent)
+    assert_close(out, ref, "verify out")
+    assert_close(lse, rlse, "verify lse")
+
+
+def test_verify_token_major_layout(ts):
+    c = _case(9, 8, 4, 777, 9)
+    parent = _random_parent(c["rng"], 9)
+    out, lse, ref, rlse = _verify_both(ts, c, parent, layout="token")
+    assert_close(out, ref, "verify out")
+    assert_close(lse, rlse, "verify lse")
+
+
+def test_verify_dominant_key_and_large_values(ts):
+    """One key with a logit about +20 above the rest, values 8x larger: the weights are peaked,
+    so rounding the probabilities would show directly in the output."""
+    c = _case(10, 8, 2, 600, 12, vscale=8.0)
+    kf = S.bf16_bits_to_f32(c["k"]).copy()
+    qf = S.bf16_bits_to_f32(c["q_tree"])
+    for h in range(2):
+        kf[h, 123 + h] = qf[3, h * 4] * (20.0 / SCALE / float(qf[3, h * 4] @ qf[3, h * 4]))
+    c["k"] = S.f32_to_bf16_bits(kf)
+    parent = _random_parent(c["rng"], 12)
+    out, lse, ref, rlse = _verify_both(ts, c, parent)
+    assert_close(out, ref, "verify out (peaked)")
+    assert_close(lse, rlse, "verify lse (peaked)")
+
+
+def test_verify_few_keys_precision(ts):
+    """Two or three comparable keys per row (tiny cache): the regime where a bf16 probability
+    would cost ~2^-9 of |v|."""
+    for n, t in [(1, 2), (2, 1), (3, 4), (0, 3)]:
+        c = _case(11 + n, 4, 2, n, t, vscale=4.0)
+        parent = np.arange(-1, t - 1, dtype=np.int32)
+        out, lse, ref, rlse = _verify_both(ts, c, parent)
+        assert_close(out, ref, "verify out (few keys n=%d t=%d)" % (n, t))
+
+
+def test_verify_split_override_and_determinism(ts):
+    """Any number of cache splits gives the same answer to tolerance; the same call twice is
+    bit-identical (no atomics anywhere)."""
+    c = _case(12, 8, 2, 3000, 16)
+    parent = _random_parent(c["rng"], 16)
+    base = None
+    try:
+        for splits in (0, 1, 3, 94):
+            ts.tune_set("verify_splits", splits)
+            out, lse, ref, rlse = _verify_both(ts, c, parent)
+            assert_close(out, ref, "verify out splits=%d" % splits)
+            out2, _, _, _ = _verify_both(ts, c, parent)
+            np.testing.assert_array_equal(out, out2)
+            base = out if base is None else base
+    finally:
+        ts.tune_set("verify_splits", 0)
