@@ -29,7 +29,23 @@ __global__ void __launch_bounds__(256) combine_kernel(const CombineParams p)
 
     f32x2 acc = {0.f, 0.f};
     float lstar = 0.f;
-    for (int pp = 0; pp < p.n_part; ++pp) {
+    int pp = 0;
+    for (; pp + 4 <= p.n_part; pp += 4) {   // four partials in flight
+        f32x2 ml[4], o[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t at = first + (int64_t)(pp + u) * pitch;
+            ml[u] = *reinterpret_cast<const f32x2 *>(p.ws_ml + at * 2);
+            o[u] = *reinterpret_cast<const f32x2 *>(p.ws_o + at * kHeadDim + lane * 2);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float w = fast_exp2(ml[u][0] - mstar);
+            lstar += w * ml[u][1];
+            acc += o[u] * w;
+        }
+    }
+    for (; pp < p.n_part; ++pp) {
         const int64_t at = first + (int64_t)pp * pitch;
         const f32x2 ml = *reinterpret_cast<const f32x2 *>(p.ws_ml + at * 2);
         const float w = fast_exp2(ml[0] - mstar);

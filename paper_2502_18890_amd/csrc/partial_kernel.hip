@@ -8,8 +8,9 @@
 // wavefront load instruction fetches four complete 256-byte rows.  All 16 keys and values of
 // the segment are requested up front (32 loads in flight per lane).  Dot products are reduced
 // across the row with DPP; since the whole segment is resident, its softmax needs no running
-// rescale.  Every segment writes (m, l, unnormalised O) per query head of the group and
-// combine_kernel merges them.  The chunks are read in place through chunk_idx: no gather copy.
+// rescale.  The 16 segments of a workgroup are merged through LDS; the workgroup writes one
+// (m, l, unnormalised O) per query head of the group and combine_kernel merges the workgroups.
+// The chunks are read in place through chunk_idx: no gather copy.
 #include "ts_device.hpp"
 #include "ts_internal.hpp"
 
@@ -31,20 +32,26 @@ __device__ __forceinline__ void unpack8(const u32x4 &raw, float (&f)[8])
 template <int G>
 __global__ void __launch_bounds__(256) partial_kernel(const PartialParams p)
 {
-    const int lane = threadIdx.x & 63;
+    __shared__ float o_lds[16][kHeadDim];
+    __shared__ float ml_lds[16][2];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
     const int c = lane & 15;                               // 16-byte slice of a row
-    const int seg_in_block = threadIdx.x >> 4;             // 16 segments per workgroup
-    const int part = blockIdx.x * 16 + seg_in_block;       // segment id within the head
+    const int seg_in_block = tid >> 4;                     // 16 segments per workgroup
+    const int segment = blockIdx.x * 16 + seg_in_block;    // segment id within the head
     const int h = blockIdx.y;
-    if (part >= p.n_part) return;                          // whole 16-lane rows leave together
+    const bool valid = segment < p.n_seg;
 
-    const int sel = part / p.segs_per_chunk;
-    const int seg = part - sel * p.segs_per_chunk;
-    const int64_t chunk = p.chunk_idx[(int64_t)h * p.n_sel + sel];
-    const int64_t t_begin = chunk * p.chunk_size + (int64_t)seg * kSegKeys;
-    int64_t t_end = (chunk + 1) * p.chunk_size;
-    if (t_end > p.n_tokens) t_end = p.n_tokens;
-    if (t_begin + kSegKeys < t_end) t_end = t_begin + kSegKeys;
+    int64_t t_begin = 0, t_end = 0;                        // empty range for an idle row
+    if (valid) {
+        const int sel = segment / p.segs_per_chunk;
+        const int seg = segment - sel * p.segs_per_chunk;
+        const int64_t chunk = p.chunk_idx[(int64_t)h * p.n_sel + sel];
+        t_begin = chunk * p.chunk_size + (int64_t)seg * kSegKeys;
+        t_end = (chunk + 1) * p.chunk_size;
+        if (t_end > p.n_tokens) t_end = p.n_tokens;
+        if (t_begin + kSegKeys < t_end) t_end = t_begin + kSegKeys;
+    }
 
     const uint16_t *kbase = p.k + (int64_t)h * p.stride_head + c * 8;
     const uint16_t *vbase = p.v + (int64_t)h * p.stride_head + c * 8;
@@ -63,7 +70,7 @@ __global__ void __launch_bounds__(256) partial_kernel(const PartialParams p)
         vraw[kk] = (t < t_end) ? *reinterpret_cast<const u32x4 *>(vbase + t * p.stride_token) : z;
     }
 
-    const int64_t prow = ((int64_t)h * p.n_part + part) * G;
+    const int64_t prow = ((int64_t)h * p.n_part + blockIdx.x) * G;
 #pragma unroll 1
     for (int jj = 0; jj < G; ++jj) {
         float qf[8];
@@ -85,24 +92,43 @@ __global__ void __launch_bounds__(256) partial_kernel(const PartialParams p)
         float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < kSegKeys; ++kk) {
-            const float pk = fast_exp2(t[kk] - m);
+            const float pk = fast_exp2(t[kk] - m);   // 0 for masked keys, also when the row is idle
             l += pk;
             float vf[8];
             unpack8(vraw[kk], vf);
 #pragma unroll
             for (int x = 0; x < 8; ++x) o[x] = fmaf(pk, vf[x], o[x]);
         }
-        float *orow = p.ws_o + (prow + jj) * kHeadDim + c * 8;
-        *reinterpret_cast<f32x4 *>(orow) = f32x4{o[0], o[1], o[2], o[3]};
-        *reinterpret_cast<f32x4 *>(orow + 4) = f32x4{o[4], o[5], o[6], o[7]};
-        if (c == 0) *reinterpret_cast<f32x2 *>(p.ws_ml + (prow + jj) * 2) = f32x2{m, l};
+        // merge the 16 segments of the workgroup (fixed order: deterministic)
+        *reinterpret_cast<f32x4 *>(&o_lds[seg_in_block][c * 8]) = f32x4{o[0], o[1], o[2], o[3]};
+        *reinterpret_cast<f32x4 *>(&o_lds[seg_in_block][c * 8 + 4]) = f32x4{o[4], o[5], o[6], o[7]};
+        if (c == 0) {
+            ml_lds[seg_in_block][0] = m;
+            ml_lds[seg_in_block][1] = l;
+        }
+        __syncthreads();
+        if (tid < kHeadDim) {
+            float mstar = kNegBig;
+#pragma unroll
+            for (int s = 0; s < 16; ++s) mstar = fmaxf(mstar, ml_lds[s][0]);
+            float acc = 0.f, lstar = 0.f;
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                const float w = fast_exp2(ml_lds[s][0] - mstar);
+                lstar = fmaf(w, ml_lds[s][1], lstar);
+                acc = fmaf(w, o_lds[s][tid], acc);
+            }
+            p.ws_o[(prow + jj) * kHeadDim + tid] = acc;
+            if (tid == 0) *reinterpret_cast<f32x2 *>(p.ws_ml + (prow + jj) * 2) = f32x2{mstar, lstar};
+        }
+        __syncthreads();
     }
 }
 
 template <int G>
 hipError_t launch_g(const PartialParams &p, hipStream_t stream)
 {
-    dim3 grid((p.n_part + 15) / 16, p.n_kv_heads);
+    dim3 grid(p.n_part, p.n_kv_heads);
     hipLaunchKernelGGL(partial_kernel<G>, grid, dim3(256), 0, stream, p);
     return hipGetLastError();
 }

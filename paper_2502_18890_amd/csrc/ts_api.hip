@@ -80,7 +80,7 @@ bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, Ve
 }
 
 struct PartialPlan {
-    int segs_per_chunk, n_part;
+    int segs_per_chunk, n_seg, n_part;
     size_t ml_offset, bytes;
 };
 
@@ -88,7 +88,8 @@ void plan_partial(int n_q_heads, int n_kv_heads, int n_sel, int chunk_size, Part
 {
     const int group = n_q_heads / n_kv_heads;
     pl->segs_per_chunk = chunk_size / 16;
-    pl->n_part = n_sel * pl->segs_per_chunk;
+    pl->n_seg = n_sel * pl->segs_per_chunk;
+    pl->n_part = (pl->n_seg + 15) / 16;
     const size_t rows_total = (size_t)n_kv_heads * pl->n_part * group;
     pl->ml_offset = round_up(rows_total * TS_HEAD_DIM * sizeof(float), 256);
     pl->bytes = pl->ml_offset + round_up(rows_total * 2 * sizeof(float), 256);
@@ -230,6 +231,7 @@ int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
     p.n_sel = n_sel;
     p.chunk_size = chunk_size;
     p.segs_per_chunk = pl.segs_per_chunk;
+    p.n_seg = pl.n_seg;
     p.n_part = pl.n_part;
     p.scale_log2 = scale * 1.4426950408889634f;
     if (ts::launch_partial(p, st) != hipSuccess) return TS_ERR_HIP;

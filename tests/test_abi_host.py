@@ -56,7 +56,7 @@ def test_workspace_bytes(binding):
     assert wb(V, 32, 32, 100000, 65) == 0                 # tree too large
     assert wb(V, 30, 8, 1000, 8) == 0                     # heads do not divide
     assert wb(V, 72, 8, 1000, 8) == 0                     # group 9 > 8
-    assert wb(P, 32, 8, 65536, 0, 65, 64) >= 8 * 65 * 4 * 4 * (128 + 2) * 4   # one partial per 16-token segment
+    assert wb(P, 32, 8, 65536, 0, 65, 64) >= 8 * 17 * 4 * (128 + 2) * 4   # one partial per 16 segments of 16 tokens
     assert wb(P, 32, 8, 65536, 0, 0, 64) == 0             # empty selection
     assert wb(P, 32, 8, 65536, 0, 65, 24) == 0            # chunk not a multiple of 16
     assert wb(99, 32, 8, 65536, 8, 65, 64) == 0
