@@ -152,6 +152,8 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
 /*
  * Tuning hook (not needed for correct results): overrides a launch-geometry choice until
  * reset with value 0.  Names: "verify_splits" (number of cache splits per KV head);
+ * "verify_impl" (1: the register-staged variant of the verification kernel instead of the
+ * direct-to-LDS one); "verify_variant" (1..4: alternative workgroup shapes);
  * "verify_stage" (1: ts_tree_verify_attn enqueues only its split kernel, 2: only its merge
  * kernel -- for timing one kernel alone; outputs are then not meaningful).  Returns TS_OK, or
  * TS_ERR_UNSUPPORTED for an unknown name or a value the kernels cannot run.  The same

@@ -12,6 +12,8 @@ constexpr int kNumCUs = 256;   // MI355X
 struct Tuning {
     int verify_splits = 0;     // 0 = heuristic
     int verify_stage = 0;      // 0 = both kernels, 1 = split kernel only, 2 = merge kernel only
+    int verify_impl = 0;       // 0 = direct-to-LDS loads, 1 = register-staged loads
+    int verify_variant = 0;    // alternative workgroup shapes of the direct-to-LDS kernel
 } g_tune;
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -60,7 +62,7 @@ bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, Ve
     if (n_tokens > 0) {
         // resident workgroups per CU of the kernel shape that covers n_rows_pad rows
         const int cap = pl->n_rows_pad;
-        const int wg_per_cu = cap <= 16 ? 8 : (cap <= 64 ? 4 : (cap <= 128 ? 2 : 1));
+        const int wg_per_cu = cap <= 32 ? 4 : (cap <= 64 ? 3 : (cap <= 128 ? 2 : 1));
         int64_t want = ((int64_t)kNumCUs * wg_per_cu + n_kv_heads - 1) / n_kv_heads;
         const int64_t cap_traffic = (n_tokens * 512 / 8) / ((int64_t)pl->n_rows_pad * 520) + 1;  // partials <= 1/8 of K/V
         if (want > cap_traffic) want = cap_traffic;
@@ -123,6 +125,16 @@ int ts_tune_set(const char *name, int value)
     if (!name || value < 0) return TS_ERR_UNSUPPORTED;
     if (strcmp(name, "verify_splits") == 0) {
         g_tune.verify_splits = value;
+        return TS_OK;
+    }
+    if (strcmp(name, "verify_impl") == 0) {
+        if (value > 1) return TS_ERR_UNSUPPORTED;
+        g_tune.verify_impl = value;
+        return TS_OK;
+    }
+    if (strcmp(name, "verify_variant") == 0) {
+        if (value > 4) return TS_ERR_UNSUPPORTED;
+        g_tune.verify_variant = value;
         return TS_OK;
     }
     if (strcmp(name, "verify_stage") == 0) {
@@ -294,7 +306,11 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
     for (int i = 0; i < 64; ++i) p.anc[i] = 0;
     for (int i = 0; i < n_tree; ++i)
         p.anc[i] = (1ull << i) | (parent[i] >= 0 ? p.anc[parent[i]] : 0ull);
-    if (g_tune.verify_stage != 2 && ts::launch_verify(p, st) != hipSuccess) return TS_ERR_HIP;
+    if (g_tune.verify_stage != 2) {
+        const hipError_t e = g_tune.verify_impl == 1 ? ts::launch_verify(p, st)
+                                                     : ts::launch_verify_dma(p, st, g_tune.verify_variant);
+        if (e != hipSuccess) return TS_ERR_HIP;
+    }
     if (g_tune.verify_stage == 1) return TS_OK;
 
     ts::CombineParams c;

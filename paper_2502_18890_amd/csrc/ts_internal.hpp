@@ -25,7 +25,8 @@ struct VerifyParams {
     uint64_t anc[64];         // anc[i] bit u set iff tree node u is i or an ancestor of i
 };
 int verify_rows_capacity(int n_rows);   // 0 if too many rows
-hipError_t launch_verify(const VerifyParams &p, hipStream_t stream);
+hipError_t launch_verify(const VerifyParams &p, hipStream_t stream);        // K/V staged through registers
+hipError_t launch_verify_dma(const VerifyParams &p, hipStream_t stream, int variant);   // K/V loaded straight into LDS
 
 // ---- partial-KV attention (partial_kernel.hip) ---------------------------------------------
 struct PartialParams {

@@ -1,0 +1,365 @@
+// Tree-masked verification attention over the full KV cache (Alg. 1 "Parallel Verification",
+// App. E of the TokenSwift paper), split along the cache, for gfx950 -- variant whose K/V
+// tiles go from HBM straight into LDS (buffer_load ... lds), several tiles ahead of compute.
+//
+// Work decomposition and arithmetic are those of verify_kernel.hip: one workgroup = one KV
+// head x one contiguous range of cached tokens (last split index = the tree tokens with the
+// ancestor mask); S^T = K.Q^T and O^T += V^T.P^T on v_mfma_f32_16x16x32_bf16 with keys on the
+// M axis, online softmax in fp32 (exp2 domain), P as bf16 hi + lo.  What differs is the data
+// path.  A tile is 32 keys: 8 KiB of K and 8 KiB of V, unpadded.  Each wavefront load
+// instruction moves four whole 256-byte rows (64 lanes x 16 B) into 1 KiB of LDS without
+// touching a VGPR, so the bytes in flight are bounded by LDS (NS stages per workgroup), not
+// by registers; the pass is HBM-bound and wants as many bytes in flight as it can get.
+// Bank conflicts are avoided by permuting the 16-byte pieces inside each row on the way in
+// (the lane that fills LDS piece `pos` of row R fetches global piece pos ^ f(R)), not by
+// padding:
+//   K rows: f(R) = R mod 16       -> the 16 rows an MFMA A-operand read touches land on 16
+//                                    different bank groups;
+//   V rows: f(R) = 8*((R/4) mod 2) -> the four rows a 64-bit V read touches (4 apart) alternate
+//                                    between the two 128-byte halves of the banks.
+// Rows past the end of the range are cut off by the buffer descriptor's byte count (the load
+// returns zeros and moves no data); the ring is cleared once at start so that a stage never
+// holds anything but finite values (a masked key contributes 0 * V).
+#include "ts_device.hpp"
+#include "ts_internal.hpp"
+
+namespace ts {
+
+namespace {
+
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+
+constexpr int kTileKeys = 32;
+constexpr int kStageBytes = kTileKeys * 512;   // K half then V half
+constexpr int kVHalf = kTileKeys * 256;
+constexpr int kQRowBytes = 272;                // padded query rows (QLDS)
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// NRB: 16-row blocks per wavefront; WR: wavefronts per workgroup (along the query rows);
+// NS: LDS stages (NS-1 tiles in flight while one is consumed); OCC: wavefronts per SIMD the
+// register budget is cut for; QLDS: query fragments live in LDS instead of registers.
+template <int NRB, int WR, int NS, int OCC, bool QLDS>
+__global__ void __launch_bounds__(64 * WR) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
+verify_dma_kernel(const VerifyParams p)
+{
+    constexpr int NT = 64 * WR;
+    constexpr int LPW = 16 / WR;   // load instructions per wavefront per tile (16 x 1 KiB = one tile)
+    static_assert(16 % WR == 0 && NS >= 2, "bad shape");
+    static_assert((NS - 2) * LPW <= 63, "too many loads in flight for vmcnt");
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: selects which blocks this wavefront loads
+    const int j = lane & 15;
+    const int quad = lane >> 4;
+    const int split = blockIdx.x;
+    const int h = blockIdx.y;
+    const bool is_tree = (split == p.n_split);
+
+    const uint16_t *kbase, *vbase;
+    int64_t tstride, t_begin, t_end;
+    if (is_tree) {
+        kbase = p.k_tree + (int64_t)h * kHeadDim;
+        vbase = p.v_tree + (int64_t)h * kHeadDim;
+        tstride = (int64_t)p.n_kv_heads * kHeadDim;
+        t_begin = 0;
+        t_end = p.n_tree;
+    } else {
+        kbase = p.k + (int64_t)h * p.stride_head;
+        vbase = p.v + (int64_t)h * p.stride_head;
+        tstride = p.stride_token;
+        t_begin = (int64_t)split * p.split_len;
+        t_end = t_begin + p.split_len < p.n_tokens ? t_begin + p.split_len : p.n_tokens;
+    }
+
+    // ---- clear the ring (and later the query area is written by its owners) ----------------
+    {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int off = tid * 16; off < NS * kStageBytes; off += NT * 16) *reinterpret_cast<u32x4 *>(lds + off) = z;
+    }
+
+    // ---- query fragments (MFMA B operand) ---------------------------------------------------
+    const int row0 = blockIdx.z * (16 * NRB * WR) + wave * NRB * 16;
+    unsigned char *qlds = lds + NS * kStageBytes + (wave * NRB * 16) * kQRowBytes;
+    bf16x8 qf[QLDS ? 1 : NRB][4];
+    uint64_t amask[NRB];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        const int row = row0 + rb * 16 + j;
+        const bool live = row < p.n_rows;
+        const int node = live ? row / p.group : 0;
+        const int jj = live ? row % p.group : 0;
+        const uint16_t *qrow = p.q + ((int64_t)node * p.n_q_heads + h * p.group + jj) * kHeadDim;
+        amask[rb] = live ? p.anc[node] : 0ull;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (live) raw = *reinterpret_cast<const u32x4 *>(qrow + s * 32 + quad * 8);
+            if (QLDS)
+                *reinterpret_cast<u32x4 *>(qlds + (rb * 16 + j) * kQRowBytes + (s * 32 + quad * 8) * 2) = raw;
+            else
+                qf[rb][s] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    // Make the query and mask loads land now, before any tile load is in flight: otherwise the
+    // first use inside the main loop would have to wait for everything issued before it,
+    // i.e. for the whole prefetched ring.
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        asm volatile("" ::"v"(amask[rb]));
+        if (!QLDS) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) asm volatile("" ::"v"(qf[rb][s]));
+        }
+    }
+    __syncthreads();   // the cleared ring is complete before any load may write into it
+
+    float m_run[NRB], l_run[NRB];
+    f32x4 oacc[NRB][2][4];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        m_run[rb] = kNegBig;
+        l_run[rb] = 0.f;
+#pragma unroll
+        for (int dg = 0; dg < 2; ++dg)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) oacc[rb][dg][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // ---- HBM -> LDS -------------------------------------------------------------------------
+    // Load instruction ii (0..15) of a tile fills LDS block ii: K rows 4ii..4ii+3 for ii < 8,
+    // V rows 4(ii-8).. for ii >= 8.  This wavefront issues ii = wave*LPW .. wave*LPW+LPW-1.
+    uint32_t goff[LPW];
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+        const int ii = wave * LPW + i;
+        const int R = 4 * (ii & 7) + quad;                       // row of the tile this lane fetches from
+        const int f = (ii >= 8) ? (((R >> 2) & 1) << 3) : (R & 15);
+        goff[i] = (uint32_t)(R * tstride * 2 + ((j ^ f) << 4));
+    }
+    auto issue_tile = [&](int64_t tile) {
+        const int64_t t0 = t_begin + tile * kTileKeys;
+        const int64_t span = t0 < t_end ? (t_end - t0 - 1) * tstride * 2 + 256 : 0;   // bytes up to the end of the last valid row
+        const uint32_t nrec = span > 0xffffffffLL ? 0xffffffffu : (uint32_t)span;
+        const int64_t tb = t0 < t_end ? t0 : t_begin;            // keep the base inside the allocation
+        const __amdgpu_buffer_rsrc_t rk =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(kbase + tb * tstride), 0, nrec, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rv =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(vbase + tb * tstride), 0, nrec, 0x00020000);
+        unsigned char *stage = lds + (int)(tile % NS) * kStageBytes;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const int ii = wave * LPW + i;                       // wave-uniform
+            const uint32_t go = goff[i];   // (a local copy: the builtin rejects an element of a template-sized array on the host pass)
+            if (ii < 8)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void_ptr)(stage + ii * 1024), 16, go, 0, 0, 0);
+            else
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void_ptr)(stage + kVHalf + (ii - 8) * 1024), 16, go, 0, 0, 0);
+        }
+    };
+
+    // per-lane LDS read offsets inside a stage
+    int koff[4];   // K: row j of a 16-row block, piece (4s + quad) ^ j
+#pragma unroll
+    for (int s = 0; s < 4; ++s) koff[s] = j * 256 + ((((s << 2) | quad) ^ j) << 4);
+    int voffl[2];  // V: row quad*4 of a 16-row block, columns 4j..4j+3 of 64-column half dg
+#pragma unroll
+    for (int dg = 0; dg < 2; ++dg)
+        voffl[dg] = kVHalf + quad * 1024 + ((((dg << 3) | (j >> 1)) ^ ((quad & 1) << 3)) << 4) + ((j & 1) << 3);
+
+    const int64_t n_tiles = (t_end - t_begin + kTileKeys - 1) / kTileKeys;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue_tile(s);   // tiles past the range load nothing but still count
+
+    for (int64_t it = 0; it < n_tiles; ++it) {
+        const int64_t t0 = t_begin + it * kTileKeys;
+        wait_vmcnt<(NS - 2) * LPW>();                 // this wavefront's pieces of tile `it` have landed
+        // ... and everyone's; all are done with tile it-1.  A bare s_barrier: __syncthreads() would add a
+        // fence that waits for every outstanding load, i.e. for the whole prefetched ring.
+        if (WR > 1) asm volatile("s_barrier" ::: "memory");
+        issue_tile(it + NS - 1);                      // refill the stage that tile it-1 occupied
+        const unsigned char *stage = lds + (int)(it % NS) * kStageBytes;
+        const bool ragged = is_tree || (t0 + kTileKeys > t_end);
+
+        // ---- S^T = K . Q^T for the 32 keys -------------------------------------------------
+        f32x4 sacc[NRB][2];
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            sacc[rb][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+            sacc[rb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(stage + kb * 4096 + koff[s]);
+#pragma unroll
+                for (int rb = 0; rb < NRB; ++rb) {
+                    const bf16x8 b = QLDS ? *reinterpret_cast<const bf16x8 *>(
+                                                qlds + (rb * 16 + j) * kQRowBytes + (s * 32 + quad * 8) * 2)
+                                          : qf[QLDS ? 0 : rb][s];
+                    sacc[rb][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, sacc[rb][kb], 0, 0, 0);
+                }
+            }
+        }
+
+        // ---- V^T operands: 8 keys x 4 consecutive columns per read, regrouped per column ----
+        bf16x8 av[2][4];
+#pragma unroll
+        for (int dg = 0; dg < 2; ++dg) {
+            u32x2 vr[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                vr[e] = *reinterpret_cast<const u32x2 *>(stage + ((e >> 2) * 16 + (e & 3)) * 256 + voffl[dg]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                u32x4 a;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const uint32_t x = vr[2 * w][i >> 1], y = vr[2 * w + 1][i >> 1];
+                    a[w] = (i & 1) ? __builtin_amdgcn_perm(y, x, 0x07060302u) : __builtin_amdgcn_perm(y, x, 0x05040100u);
+                }
+                av[dg][i] = __builtin_bit_cast(bf16x8, a);
+            }
+        }
+
+        // ---- per 16-row block: online softmax, then O^T += V^T . P^T -------------------------
+        // This lane owns keys kb*16 + quad*4 + v (e = kb*4 + v) of query row j.
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            float t[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) t[e] = sacc[rb][e >> 2][e & 3] * p.scale_log2;
+            if (ragged) {
+                // bit b of vm: key quad*4 + b of this tile may be attended by row j
+                const uint64_t tile_ok = is_tree ? (amask[rb] >> t0)
+                                                 : (t_end - t0 >= 64 ? ~0ull : ((1ull << (t_end - t0)) - 1ull));
+                const uint32_t vm = (uint32_t)(tile_ok >> (quad * 4));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) t[e] = ((vm >> ((e >> 2) * 16 + (e & 3))) & 1u) ? t[e] : -INFINITY;
+            }
+            float mloc = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+            mloc = xrow_max(mloc);
+            const float m_new = fmaxf(m_run[rb], mloc);
+            if (__builtin_amdgcn_ballot_w64(m_new != m_run[rb]) != 0ull) {   // some row saw a new maximum
+                const float alpha = fast_exp2(m_run[rb] - m_new);
+                l_run[rb] *= alpha;
+#pragma unroll
+                for (int dg = 0; dg < 2; ++dg)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) oacc[rb][dg][i] *= alpha;
+                m_run[rb] = m_new;
+            }
+            float pe[8], psum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                pe[e] = fast_exp2(t[e] - m_new);
+                psum += pe[e];
+            }
+            l_run[rb] += psum;
+            u32x4 hi, lo;   // P = hi + lo, both bf16: the product keeps ~16 bits of each weight
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const uint32_t hw = pack_bf16(pe[2 * w], pe[2 * w + 1]);
+                hi[w] = hw;
+                lo[w] = pack_bf16(pe[2 * w] - bf16lo_to_f32(hw), pe[2 * w + 1] - bf16hi_to_f32(hw));
+            }
+            const bf16x8 p_hi = __builtin_bit_cast(bf16x8, hi);
+            const bf16x8 p_lo = __builtin_bit_cast(bf16x8, lo);
+#pragma unroll
+            for (int dg = 0; dg < 2; ++dg)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    oacc[rb][dg][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dg][i], p_hi, oacc[rb][dg][i], 0, 0, 0);
+#pragma unroll
+            for (int dg = 0; dg < 2; ++dg)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    oacc[rb][dg][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dg][i], p_lo, oacc[rb][dg][i], 0, 0, 0);
+        }
+    }
+    wait_vmcnt<0>();   // drain the loads issued past the range before the workgroup's LDS is released
+
+    // ---- write the partial: (m, l) and unnormalised O for every live row ----------------------
+    const int n_part = p.n_split + 1;
+    const int64_t part = ((int64_t)h * n_part + split) * p.n_rows_pad;
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        const int row = row0 + rb * 16 + j;
+        const float l_tot = xrow_sum(l_run[rb]);
+        if (row < p.n_rows) {
+            if (quad == 0) {
+                f32x2 ml = {m_run[rb], l_tot};
+                *reinterpret_cast<f32x2 *>(p.ws_ml + (part + row) * 2) = ml;
+            }
+            float *orow = p.ws_o + (part + row) * kHeadDim;
+            // this lane holds columns dg*64 + quad*16 + 4v + i
+#pragma unroll
+            for (int dg = 0; dg < 2; ++dg)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    f32x4 o = {oacc[rb][dg][0][v], oacc[rb][dg][1][v], oacc[rb][dg][2][v], oacc[rb][dg][3][v]};
+                    *reinterpret_cast<f32x4 *>(orow + dg * 64 + quad * 16 + 4 * v) = o;
+                }
+        }
+    }
+}
+
+template <int NRB, int WR, int NS, int OCC, bool QLDS>
+hipError_t launch_one(const VerifyParams &p, hipStream_t stream)
+{
+    constexpr int kRows = 16 * NRB * WR;
+    constexpr int lds_bytes = NS * kStageBytes + (QLDS ? kRows * kQRowBytes : 0);
+    static_assert(lds_bytes <= 160 * 1024, "LDS budget");
+    static bool attr_set = false;
+    if (lds_bytes > 64 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(verify_dma_kernel<NRB, WR, NS, OCC, QLDS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid(p.n_split + 1, p.n_kv_heads, (p.n_rows + kRows - 1) / kRows);
+    hipLaunchKernelGGL((verify_dma_kernel<NRB, WR, NS, OCC, QLDS>), grid, dim3(64 * WR), lds_bytes, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_verify_dma(const VerifyParams &p, hipStream_t stream, int variant)
+{
+    switch (verify_rows_capacity(p.n_rows)) {
+        case 16: return launch_one<1, 1, 2, 2, false>(p, stream);
+        case 32:
+            switch (variant) {
+                case 1: return launch_one<1, 2, 3, 2, false>(p, stream);
+                case 2: return launch_one<1, 2, 4, 2, false>(p, stream);
+                case 3: return launch_one<2, 1, 2, 2, false>(p, stream);
+                case 4: return launch_one<2, 1, 4, 2, false>(p, stream);
+                default: return launch_one<1, 2, 2, 2, false>(p, stream);   // 4 workgroups per CU
+            }
+        case 64: return launch_one<2, 2, 3, 2, false>(p, stream);
+        case 96: return launch_one<3, 2, 4, 1, false>(p, stream);
+        case 128:
+            switch (variant) {
+                case 1: return launch_one<2, 4, 4, 2, false>(p, stream);
+                case 2: return launch_one<2, 4, 8, 2, false>(p, stream);
+                case 3: return launch_one<4, 2, 4, 1, false>(p, stream);
+                default: return launch_one<2, 4, 2, 2, false>(p, stream);
+            }
+        case 192: return launch_one<3, 4, 8, 1, false>(p, stream);
+        case 256: return launch_one<4, 4, 8, 1, false>(p, stream);
+        case 320: return launch_one<5, 4, 4, 1, true>(p, stream);
+        case 384: return launch_one<6, 4, 3, 1, true>(p, stream);
+        case 512: return launch_one<4, 4, 8, 1, false>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace ts

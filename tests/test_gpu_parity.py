@@ -245,3 +245,22 @@ def test_verify_split_override_and_determinism(ts):
             base = out if base is None else base
     finally:
         ts.tune_set("verify_splits", 0)
+
+
+@pytest.mark.parametrize("impl,variant", [(1, 0), (0, 0), (0, 1), (0, 2), (0, 3), (0, 4)])
+@pytest.mark.parametrize("hq,hkv,n,t", [(8, 2, 1000, 8), (32, 8, 2085, 32), (12, 2, 999, 16), (40, 8, 700, 64),
+                                        (4, 4, 130, 3), (48, 8, 333, 64), (64, 8, 200, 64)])
+def test_verify_kernel_variants(ts, impl, variant, hq, hkv, n, t):
+    """Both data paths of the verification kernel (register-staged and direct-to-LDS) and the
+    alternative workgroup shapes must all match the oracle."""
+    c = _case(21, hq, hkv, n, t)
+    parent = _random_parent(c["rng"], t)
+    try:
+        ts.tune_set("verify_impl", impl)
+        ts.tune_set("verify_variant", variant)
+        out, lse, ref, rlse = _verify_both(ts, c, parent)
+    finally:
+        ts.tune_set("verify_impl", 0)
+        ts.tune_set("verify_variant", 0)
+    assert_close(out, ref, "verify out impl=%d variant=%d" % (impl, variant))
+    assert_close(lse, rlse, "verify lse impl=%d variant=%d" % (impl, variant))
