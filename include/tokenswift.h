@@ -122,7 +122,8 @@ int ts_topk_chunks(const float *scores, int n_kv_heads, int n_chunks, int n_sink
  *   out        fp32 [n_q_heads][128]
  *   lse        fp32 [n_q_heads], natural-log sum of exponentials of the scaled logits; nullable
  *   workspace  >= ts_workspace_bytes(TS_OP_PARTIAL_ATTN, ...) bytes, 256-byte aligned
- * chunk_size: multiple of 16, 16..1024.  Errors as above plus n_sel < 1.
+ * chunk_size: multiple of 16, 16..1024.  scale must be positive and finite (TS_ERR_UNSUPPORTED
+ * otherwise).  Errors as above plus n_sel < 1.
  */
 int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
                        const int32_t *chunk_idx, int n_sel, int chunk_size, float scale,
@@ -141,7 +142,8 @@ int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
  *   out             fp32 [n_tree][n_q_heads][128]
  *   lse             fp32 [n_tree][n_q_heads]; nullable
  *   workspace       >= ts_workspace_bytes(TS_OP_TREE_VERIFY, ...) bytes, 256-byte aligned
- * n_tree: 1..TS_MAX_TREE.  kv->n_tokens may be 0 (then kv->k, kv->v may be NULL).
+ * n_tree: 1..TS_MAX_TREE.  kv->n_tokens may be 0 (then kv->k, kv->v may be NULL).  scale must be
+ * positive and finite (TS_ERR_UNSUPPORTED otherwise).
  * Errors: TS_ERR_TREE for a malformed parent array; the others as above.
  */
 int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,

@@ -14,7 +14,7 @@ from typing import Optional, Sequence
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libtokenswift_hip.so")
+_LIB_PATH = os.environ.get("TOKENSWIFT_LIB", os.path.join(_PKG, "libtokenswift_hip.so"))   # override: another build of the same ABI
 
 OP_PARTIAL_ATTN = 1
 OP_TREE_VERIFY = 2

@@ -97,6 +97,9 @@ void plan_partial(int n_q_heads, int n_kv_heads, int n_sel, int chunk_size, Part
     pl->bytes = pl->ml_offset + round_up(rows_total * 2 * sizeof(float), 256);
 }
 
+// the attention kernels take row maxima before scaling the logits
+bool scale_ok(float scale) { return scale > 0.f && scale < 3.0e38f; }
+
 bool partial_chunk_ok(int chunk_size) { return chunk_size >= 16 && chunk_size <= 1024 && chunk_size % 16 == 0; }
 
 }  // namespace
@@ -220,7 +223,7 @@ int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
     int group = 0;
     if ((rc = check_heads(n_q_heads, kv->n_kv_heads, &group)) != TS_OK) return rc;
     if (n_sel < 1) return TS_ERR_SHAPE;
-    if (!partial_chunk_ok(chunk_size)) return TS_ERR_UNSUPPORTED;
+    if (!partial_chunk_ok(chunk_size) || !scale_ok(scale)) return TS_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(out)) return TS_ERR_ALIGN;
     PartialPlan pl;
     plan_partial(n_q_heads, kv->n_kv_heads, n_sel, chunk_size, &pl);
@@ -273,7 +276,7 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
     int group = 0;
     if ((rc = check_heads(n_q_heads, kv->n_kv_heads, &group)) != TS_OK) return rc;
     if (n_tree < 1) return TS_ERR_SHAPE;
-    if (n_tree > TS_MAX_TREE) return TS_ERR_UNSUPPORTED;
+    if (n_tree > TS_MAX_TREE || !scale_ok(scale)) return TS_ERR_UNSUPPORTED;
     for (int i = 0; i < n_tree; ++i)
         if (parent[i] < -1 || parent[i] >= i) return TS_ERR_TREE;
     if (!aligned16(q_tree) || !aligned16(k_tree) || !aligned16(v_tree) || !aligned16(out)) return TS_ERR_ALIGN;

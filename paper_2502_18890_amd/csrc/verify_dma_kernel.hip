@@ -20,6 +20,8 @@
 // Rows past the end of the range are cut off by the buffer descriptor's byte count (the load
 // returns zeros and moves no data); the ring is cleared once at start so that a stage never
 // holds anything but finite values (a masked key contributes 0 * V).
+#include <type_traits>
+
 #include "ts_device.hpp"
 #include "ts_internal.hpp"
 
@@ -79,16 +81,19 @@ verify_dma_kernel(const VerifyParams p)
         t_end = t_begin + p.split_len < p.n_tokens ? t_begin + p.split_len : p.n_tokens;
     }
 
-    // ---- clear the ring (and later the query area is written by its owners) ----------------
+    // ---- clear the ring --------------------------------------------------------------------
     {
         const u32x4 z = {0u, 0u, 0u, 0u};
         for (int off = tid * 16; off < NS * kStageBytes; off += NT * 16) *reinterpret_cast<u32x4 *>(lds + off) = z;
     }
+    // the cleared ring is complete before any load may write into it (LDS traffic only: no
+    // need to wait for global memory here)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-    // ---- query fragments (MFMA B operand) ---------------------------------------------------
+    // ---- query fragments (MFMA B operand): loads issued now, awaited after the prefetch is out --
     const int row0 = blockIdx.z * (16 * NRB * WR) + wave * NRB * 16;
     unsigned char *qlds = lds + NS * kStageBytes + (wave * NRB * 16) * kQRowBytes;
-    bf16x8 qf[QLDS ? 1 : NRB][4];
+    u32x4 qraw[NRB][4];
     uint64_t amask[NRB];
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
@@ -102,24 +107,9 @@ verify_dma_kernel(const VerifyParams p)
         for (int s = 0; s < 4; ++s) {
             u32x4 raw = {0u, 0u, 0u, 0u};
             if (live) raw = *reinterpret_cast<const u32x4 *>(qrow + s * 32 + quad * 8);
-            if (QLDS)
-                *reinterpret_cast<u32x4 *>(qlds + (rb * 16 + j) * kQRowBytes + (s * 32 + quad * 8) * 2) = raw;
-            else
-                qf[rb][s] = __builtin_bit_cast(bf16x8, raw);
+            qraw[rb][s] = raw;
         }
     }
-    // Make the query and mask loads land now, before any tile load is in flight: otherwise the
-    // first use inside the main loop would have to wait for everything issued before it,
-    // i.e. for the whole prefetched ring.
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        asm volatile("" ::"v"(amask[rb]));
-        if (!QLDS) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) asm volatile("" ::"v"(qf[rb][s]));
-        }
-    }
-    __syncthreads();   // the cleared ring is complete before any load may write into it
 
     float m_run[NRB], l_run[NRB];
     f32x4 oacc[NRB][2][4];
@@ -178,17 +168,33 @@ verify_dma_kernel(const VerifyParams p)
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s) issue_tile(s);   // tiles past the range load nothing but still count
 
-    for (int64_t it = 0; it < n_tiles; ++it) {
-        const int64_t t0 = t_begin + it * kTileKeys;
-        wait_vmcnt<(NS - 2) * LPW>();                 // this wavefront's pieces of tile `it` have landed
-        // ... and everyone's; all are done with tile it-1.  A bare s_barrier: __syncthreads() would add a
-        // fence that waits for every outstanding load, i.e. for the whole prefetched ring.
-        if (WR > 1) asm volatile("s_barrier" ::: "memory");
-        issue_tile(it + NS - 1);                      // refill the stage that tile it-1 occupied
-        const unsigned char *stage = lds + (int)(it % NS) * kStageBytes;
-        const bool ragged = is_tree || (t0 + kTileKeys > t_end);
+    // Now wait for the query and mask loads (older than every tile load, so the tile loads stay
+    // in flight) -- here, not at their first use inside the main loop, where the wait would be
+    // for everything issued before it, i.e. for the whole prefetched ring.
+    bf16x8 qf[QLDS ? 1 : NRB][4];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        asm volatile("" ::"v"(amask[rb]));
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            asm volatile("" ::"v"(qraw[rb][s]));
+            if (QLDS)   // each wavefront later reads back only what it wrote itself
+                *reinterpret_cast<u32x4 *>(qlds + (rb * 16 + j) * kQRowBytes + (s * 32 + quad * 8) * 2) = qraw[rb][s];
+            else
+                qf[rb][s] = __builtin_bit_cast(bf16x8, qraw[rb][s]);
+        }
+    }
 
-        // ---- S^T = K . Q^T for the 32 keys -------------------------------------------------
+    // One 32-key tile against all of this wavefront's rows.  RAGGED tiles (the last one of a
+    // range, every tile of the tree split) mask keys; full tiles carry no masking code at all.
+    // The body is laid out as three straight-line blocks so that the scheduler can overlap
+    // matrix and vector work: (1) S^T MFMAs with the V^T operand regrouping, (2) row maxima of
+    // all row blocks and one ballot (rescaling is a rare side branch), (3) exp/pack of row
+    // block rb+1 against the PV MFMAs of row block rb.
+    auto process_tile = [&](auto ragged_tag, const unsigned char *stage, int64_t t0) {
+        constexpr bool RAGGED = decltype(ragged_tag)::value;
+
+        // ---- (1) S^T = K . Q^T for the 32 keys; V^T operands ---------------------------------
         f32x4 sacc[NRB][2];
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
@@ -209,8 +215,7 @@ verify_dma_kernel(const VerifyParams p)
                 }
             }
         }
-
-        // ---- V^T operands: 8 keys x 4 consecutive columns per read, regrouped per column ----
+        // 8 keys x 4 consecutive columns per read, regrouped into one column x 8 keys per operand
         bf16x8 av[2][4];
 #pragma unroll
         for (int dg = 0; dg < 2; ++dg) {
@@ -230,61 +235,93 @@ verify_dma_kernel(const VerifyParams p)
             }
         }
 
-        // ---- per 16-row block: online softmax, then O^T += V^T . P^T -------------------------
+        // ---- (2) row maxima (raw logits; scale > 0 commutes with max) --------------------------
         // This lane owns keys kb*16 + quad*4 + v (e = kb*4 + v) of query row j.
+        float m_new[NRB];
+        bool moved = false;
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
-            float t[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) t[e] = sacc[rb][e >> 2][e & 3] * p.scale_log2;
-            if (ragged) {
+            if (RAGGED) {
                 // bit b of vm: key quad*4 + b of this tile may be attended by row j
                 const uint64_t tile_ok = is_tree ? (amask[rb] >> t0)
                                                  : (t_end - t0 >= 64 ? ~0ull : ((1ull << (t_end - t0)) - 1ull));
                 const uint32_t vm = (uint32_t)(tile_ok >> (quad * 4));
 #pragma unroll
-                for (int e = 0; e < 8; ++e) t[e] = ((vm >> ((e >> 2) * 16 + (e & 3))) & 1u) ? t[e] : -INFINITY;
+                for (int e = 0; e < 8; ++e)
+                    if (!((vm >> ((e >> 2) * 16 + (e & 3))) & 1u)) sacc[rb][e >> 2][e & 3] = -INFINITY;
             }
-            float mloc = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+            const f32x4 s0 = sacc[rb][0], s1 = sacc[rb][1];
+            float mloc = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])), fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
             mloc = xrow_max(mloc);
-            const float m_new = fmaxf(m_run[rb], mloc);
-            if (__builtin_amdgcn_ballot_w64(m_new != m_run[rb]) != 0ull) {   // some row saw a new maximum
-                const float alpha = fast_exp2(m_run[rb] - m_new);
+            m_new[rb] = fmaxf(m_run[rb], mloc * p.scale_log2);
+            moved |= (m_new[rb] != m_run[rb]);
+        }
+        if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {   // some row of this wavefront saw a new maximum
+#pragma unroll
+            for (int rb = 0; rb < NRB; ++rb) {
+                const float alpha = fast_exp2(m_run[rb] - m_new[rb]);
                 l_run[rb] *= alpha;
 #pragma unroll
                 for (int dg = 0; dg < 2; ++dg)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) oacc[rb][dg][i] *= alpha;
-                m_run[rb] = m_new;
+                m_run[rb] = m_new[rb];
             }
+        }
+
+        // ---- (3) P = exp2(scale*s - m), split hi + lo (both bf16), O^T += V^T . P^T -------------
+        // Software-pipelined over the row blocks: the vector work that makes P of block rb+1 sits
+        // in the same scheduling region as the matrix work that consumes P of block rb.
+        auto make_p = [&](int rb, bf16x8 &p_hi, bf16x8 &p_lo) {
             float pe[8], psum = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                pe[e] = fast_exp2(t[e] - m_new);
+                pe[e] = fast_exp2(fmaf(sacc[rb][e >> 2][e & 3], p.scale_log2, -m_run[rb]));
                 psum += pe[e];
             }
             l_run[rb] += psum;
-            u32x4 hi, lo;   // P = hi + lo, both bf16: the product keeps ~16 bits of each weight
+            u32x4 hi, lo;   // the product keeps ~16 bits of each weight
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
                 const uint32_t hw = pack_bf16(pe[2 * w], pe[2 * w + 1]);
                 hi[w] = hw;
                 lo[w] = pack_bf16(pe[2 * w] - bf16lo_to_f32(hw), pe[2 * w + 1] - bf16hi_to_f32(hw));
             }
-            const bf16x8 p_hi = __builtin_bit_cast(bf16x8, hi);
-            const bf16x8 p_lo = __builtin_bit_cast(bf16x8, lo);
+            p_hi = __builtin_bit_cast(bf16x8, hi);
+            p_lo = __builtin_bit_cast(bf16x8, lo);
+        };
+        bf16x8 p_hi[2], p_lo[2];
+        make_p(0, p_hi[0], p_lo[0]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            if (rb + 1 < NRB) make_p(rb + 1, p_hi[(rb + 1) & 1], p_lo[(rb + 1) & 1]);
 #pragma unroll
             for (int dg = 0; dg < 2; ++dg)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    oacc[rb][dg][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dg][i], p_hi, oacc[rb][dg][i], 0, 0, 0);
+                    oacc[rb][dg][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dg][i], p_hi[rb & 1], oacc[rb][dg][i], 0, 0, 0);
 #pragma unroll
             for (int dg = 0; dg < 2; ++dg)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    oacc[rb][dg][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dg][i], p_lo, oacc[rb][dg][i], 0, 0, 0);
+                    oacc[rb][dg][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dg][i], p_lo[rb & 1], oacc[rb][dg][i], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-    }
+    };
+
+    // full tiles first, then (cache ranges) at most one ragged tile; the tree split is all ragged
+    auto step = [&](auto ragged_tag, int64_t it) {
+        wait_vmcnt<(NS - 2) * LPW>();                 // this wavefront's pieces of tile `it` have landed
+        // ... and everyone's; all are done with tile it-1.  A bare s_barrier: __syncthreads() would add a
+        // fence that waits for every outstanding load, i.e. for the whole prefetched ring.
+        if (WR > 1) asm volatile("s_barrier" ::: "memory");
+        issue_tile(it + NS - 1);                      // refill the stage that tile it-1 occupied
+        process_tile(ragged_tag, lds + (int)(it % NS) * kStageBytes, t_begin + it * kTileKeys);
+    };
+    const int64_t n_full = is_tree ? 0 : (t_end - t_begin) / kTileKeys;
+    for (int64_t it = 0; it < n_full; ++it) step(std::false_type{}, it);
+    for (int64_t it = n_full; it < n_tiles; ++it) step(std::true_type{}, it);
     wait_vmcnt<0>();   // drain the loads issued past the range before the workgroup's LDS is released
 
     // ---- write the partial: (m, l) and unnormalised O for every live row ----------------------
@@ -351,12 +388,21 @@ hipError_t launch_verify_dma(const VerifyParams &p, hipStream_t stream, int vari
                 case 1: return launch_one<2, 4, 4, 2, false>(p, stream);
                 case 2: return launch_one<2, 4, 8, 2, false>(p, stream);
                 case 3: return launch_one<4, 2, 4, 1, false>(p, stream);
+                case 4: return launch_one<1, 8, 2, 4, false>(p, stream);
                 default: return launch_one<2, 4, 2, 2, false>(p, stream);
             }
         case 192: return launch_one<3, 4, 8, 1, false>(p, stream);
         case 256: return launch_one<4, 4, 8, 1, false>(p, stream);
-        case 320: return launch_one<5, 4, 4, 1, true>(p, stream);
-        case 384: return launch_one<6, 4, 3, 1, true>(p, stream);
+        case 320:
+            switch (variant) {
+                case 1: return launch_one<3, 8, 3, 2, true>(p, stream);
+                default: return launch_one<5, 4, 4, 1, true>(p, stream);
+            }
+        case 384:
+            switch (variant) {
+                case 1: return launch_one<3, 8, 3, 2, true>(p, stream);
+                default: return launch_one<6, 4, 3, 1, true>(p, stream);
+            }
         case 512: return launch_one<4, 4, 8, 1, false>(p, stream);
         default: return hipErrorInvalidValue;
     }

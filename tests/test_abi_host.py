@@ -97,9 +97,11 @@ def test_scores_and_topk_reject_bad_arguments(lib, binding):
 def test_attention_calls_reject_bad_arguments(lib, binding):
     q, idx, out, ws = 0x3000, 0x5000, 0x4000, 0x10000
     big = 1 << 30
-    pa = lambda view=None, hq=4, n_sel=3, chunk=64, ws_=ws, wsb=big, q_=q, idx_=idx, out_=out: lib.ts_partial_kv_attn(
-        ctypes.byref(view if view is not None else _view(binding)), q_, hq, idx_, n_sel, chunk, 1.0, out_, None,
+    pa = lambda view=None, hq=4, n_sel=3, chunk=64, ws_=ws, wsb=big, q_=q, idx_=idx, out_=out, scale=1.0: lib.ts_partial_kv_attn(
+        ctypes.byref(view if view is not None else _view(binding)), q_, hq, idx_, n_sel, chunk, scale, out_, None,
         ws_, wsb, None)
+    assert pa(scale=0.0) == TS_ERR_UNSUPPORTED and pa(scale=-1.0) == TS_ERR_UNSUPPORTED
+    assert pa(scale=float("inf")) == TS_ERR_UNSUPPORTED and pa(scale=float("nan")) == TS_ERR_UNSUPPORTED
     assert pa(idx_=None) == TS_ERR_NULL and pa(out_=None) == TS_ERR_NULL and pa(q_=None) == TS_ERR_NULL
     assert pa(view=_view(binding, v=None)) == TS_ERR_NULL
     assert pa(n_sel=0) == TS_ERR_SHAPE
@@ -108,10 +110,12 @@ def test_attention_calls_reject_bad_arguments(lib, binding):
     assert pa(ws_=ws + 16) == TS_ERR_WORKSPACE                  # not 256-byte aligned
     assert pa(out_=out + 4) == TS_ERR_ALIGN
 
-    def tv(parent, view=None, hq=4, ws_=ws, wsb=big, kt=0x6000, out_=out):
+    def tv(parent, view=None, hq=4, ws_=ws, wsb=big, kt=0x6000, out_=out, scale=1.0):
         par = (ctypes.c_int32 * len(parent))(*parent) if parent is not None else None
         return lib.ts_tree_verify_attn(ctypes.byref(view if view is not None else _view(binding)), q, hq, kt, 0x7000,
-                                       par, len(parent) if parent is not None else 4, 1.0, out_, None, ws_, wsb, None)
+                                       par, len(parent) if parent is not None else 4, scale, out_, None, ws_, wsb, None)
+    assert tv([-1, 0], scale=0.0) == TS_ERR_UNSUPPORTED and tv([-1, 0], scale=-0.5) == TS_ERR_UNSUPPORTED
+    assert tv([-1, 0], scale=float("nan")) == TS_ERR_UNSUPPORTED
     assert tv(None) == TS_ERR_NULL
     assert tv([-1, 0], kt=None) == TS_ERR_NULL
     assert tv([0, 0]) == TS_ERR_TREE            # a node cannot be its own parent
