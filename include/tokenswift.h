@@ -47,7 +47,8 @@ typedef enum {
 #define TS_HEAD_DIM 128
 #define TS_MAX_TREE 64        /* tree nodes per call (one 64-bit ancestor mask per node) */
 #define TS_MAX_GROUP 8        /* query heads per KV head */
-#define TS_MAX_CHUNKS 8192    /* chunks per KV head that ts_topk_chunks can rank */
+#define TS_MAX_CHUNKS (1 << 20)  /* chunks per KV head that ts_topk_chunks can rank */
+#define TS_MAX_TOPK 8192      /* chunks per KV head that ts_topk_chunks can select (k) */
 
 /* One layer's KV cache, as the paper's C_full (Alg. 1): n_tokens cached (key, value) pairs
  * for each of n_kv_heads heads.  Element (h, t, x) of K lives at
@@ -105,7 +106,7 @@ int ts_chunk_scores(const ts_kv_view *kv, const void *q, int n_q_heads, int chun
  * lower chunk index (-0 equals +0); NaN scores rank below every number, by index.
  *   scores   fp32 [n_kv_heads][n_chunks]
  *   idx_out  int32 [n_kv_heads][n_sink_chunks + k]
- * Errors: n_chunks < 1 or > TS_MAX_CHUNKS, n_sink_chunks < 0, k < 0,
+ * Errors: n_chunks < 1 or > TS_MAX_CHUNKS, k > TS_MAX_TOPK, n_sink_chunks < 0, k < 0,
  * n_sink_chunks + k > n_chunks, n_sink_chunks + k == 0.
  */
 int ts_topk_chunks(const float *scores, int n_kv_heads, int n_chunks, int n_sink_chunks, int k,

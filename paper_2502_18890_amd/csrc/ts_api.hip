@@ -201,7 +201,7 @@ int ts_topk_chunks(const float *scores, int n_kv_heads, int n_chunks, int n_sink
     if (!scores || !idx_out) return TS_ERR_NULL;
     if (n_kv_heads < 1 || n_chunks < 1 || n_sink_chunks < 0 || k < 0) return TS_ERR_SHAPE;
     if ((int64_t)n_sink_chunks + k > n_chunks || n_sink_chunks + k < 1) return TS_ERR_SHAPE;
-    if (n_chunks > TS_MAX_CHUNKS) return TS_ERR_UNSUPPORTED;
+    if (n_chunks > TS_MAX_CHUNKS || k > TS_MAX_TOPK) return TS_ERR_UNSUPPORTED;
     ts::TopkParams p;
     p.scores = scores;
     p.idx_out = idx_out;

@@ -91,7 +91,8 @@ def test_scores_and_topk_reject_bad_arguments(lib, binding):
     assert tk(sink=8, k=3) == TS_ERR_SHAPE
     assert tk(sink=0, k=0) == TS_ERR_SHAPE
     assert tk(k=-1) == TS_ERR_SHAPE and tk(sink=-1) == TS_ERR_SHAPE and tk(n_chunks=0) == TS_ERR_SHAPE
-    assert tk(n_chunks=8193) == TS_ERR_UNSUPPORTED
+    assert tk(n_chunks=(1 << 20) + 1) == TS_ERR_UNSUPPORTED
+    assert tk(n_chunks=20000, k=8193) == TS_ERR_UNSUPPORTED
 
 
 def test_attention_calls_reject_bad_arguments(lib, binding):

@@ -73,7 +73,10 @@ def test_chunk_scores_token_major_layout(ts):
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("hkv,n_chunks,n_sink,k", [(1, 64, 1, 8), (2, 256, 1, 64), (8, 1024, 1, 64), (32, 1563, 1, 64),
                                                    (8, 1600, 1, 128), (3, 1, 1, 0), (3, 1, 0, 1), (2, 2, 0, 2),
-                                                   (2, 17, 3, 14), (1, 8192, 2, 512), (4, 100, 0, 100), (2, 33, 33, 0)])
+                                                   (2, 17, 3, 14), (1, 8192, 2, 512), (4, 100, 0, 100), (2, 33, 33, 0),
+                                                   (2, 300, 0, 256), (2, 300, 1, 257), (3, 8193, 0, 4096), (2, 9000, 3, 100),
+                                                   (1, 100000, 0, 4096), (2, 70000, 64, 8192), (2, 255, 0, 1), (2, 257, 1, 256),
+                                                   (1, 65537, 1, 17), (2, 5000, 0, 5000)])
 def test_topk_matches_oracle_bit_exact(ts, hkv, n_chunks, n_sink, k):
     import torch
     rng = np.random.default_rng(3)
