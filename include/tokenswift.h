@@ -45,7 +45,7 @@ typedef enum {
 
 /* Limits of the kernels. */
 #define TS_HEAD_DIM 128
-#define TS_MAX_TREE 64        /* tree nodes per call (one 64-bit ancestor mask per node) */
+#define TS_MAX_TREE 128       /* tree nodes per call (one 128-bit ancestor mask per node) */
 #define TS_MAX_GROUP 8        /* query heads per KV head */
 #define TS_MAX_CHUNKS (1 << 20)  /* chunks per KV head that ts_topk_chunks can rank */
 #define TS_MAX_TOPK 8192      /* chunks per KV head that ts_topk_chunks can select (k) */

@@ -13,7 +13,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libtokenswift_hip.so")
-SOURCES = ["ts_api.hip", "verify_kernel.hip", "verify_dma_kernel.hip", "partial_kernel.hip", "combine_kernel.hip",
+SOURCES = ["ts_api.hip", "verify_dma_kernel.hip", "verify_wide_kernel.hip", "partial_kernel.hip", "combine_kernel.hip",
            "scores_kernel.hip", "topk_kernel.hip"]
 # packed-fp32 instructions are switched off for all device code
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

@@ -12,8 +12,7 @@ constexpr int kNumCUs = 256;   // MI355X
 struct Tuning {
     int verify_splits = 0;     // 0 = heuristic
     int verify_stage = 0;      // 0 = both kernels, 1 = split kernel only, 2 = merge kernel only
-    int verify_impl = 0;       // 0 = direct-to-LDS loads, 1 = register-staged loads
-    int verify_variant = 0;    // alternative workgroup shapes of the direct-to-LDS kernel
+    int verify_variant = 0;    // 0 = default kernel shapes; 1, 2 = alternatives (see verify_shape)
 } g_tune;
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -43,28 +42,28 @@ int check_heads(int n_q_heads, int n_kv_heads, int *group)
 
 // ---- geometry of the verification pass ------------------------------------------------------
 struct VerifyPlan {
+    ts::VerifyShape shape;
     int n_rows, n_rows_pad, n_split;
     int64_t split_len;
     size_t ml_offset, bytes;
 };
 
-// Splits of the cache: enough workgroups to keep every CU's latency-hiding slots full,
-// but few enough that the fp32 partials (520 B per row and split) stay a small fraction of
-// the K/V bytes (512 B per cached token).
+// Splits of the cache: as many workgroups as the chip holds at once (so that the grid runs as
+// one resident wave with every CU's latency-hiding slots full), but few enough that the fp32
+// partials (520 B per row and split) stay a small fraction of the K/V bytes (512 B per token).
 bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, VerifyPlan *pl)
 {
     const int group = n_q_heads / n_kv_heads;
     pl->n_rows = group * n_tree;
-    pl->n_rows_pad = ts::verify_rows_capacity(pl->n_rows);
-    if (pl->n_rows_pad == 0) return false;
+    pl->n_rows_pad = (pl->n_rows + 15) / 16 * 16;
+    if (!ts::verify_shape(pl->n_rows, g_tune.verify_variant, &pl->shape)) return false;
     int n_split = 0;
     int64_t split_len = 32;
     if (n_tokens > 0) {
-        // resident workgroups per CU of the kernel shape that covers n_rows_pad rows
-        const int cap = pl->n_rows_pad;
-        const int wg_per_cu = cap <= 32 ? 4 : (cap <= 64 ? 3 : (cap <= 128 ? 2 : 1));
-        int64_t want = ((int64_t)kNumCUs * wg_per_cu + n_kv_heads - 1) / n_kv_heads;
-        const int64_t cap_traffic = (n_tokens * 512 / 8) / ((int64_t)pl->n_rows_pad * 520) + 1;  // partials <= 1/8 of K/V
+        const int row_tiles = (pl->n_rows + pl->shape.rows_per_wg - 1) / pl->shape.rows_per_wg;
+        const int64_t per_split = (int64_t)n_kv_heads * row_tiles;          // workgroups per split index
+        int64_t want = (int64_t)kNumCUs * pl->shape.wg_per_cu / per_split - 1;   // - 1: the tree split
+        const int64_t cap_traffic = (n_tokens * 512 / 4) / ((int64_t)pl->n_rows_pad * 520) + 1;  // partials <= 1/4 of K/V
         if (want > cap_traffic) want = cap_traffic;
         if (g_tune.verify_splits > 0) want = g_tune.verify_splits;
         const int64_t max_split = (n_tokens + 31) / 32;
@@ -104,6 +103,31 @@ bool partial_chunk_ok(int chunk_size) { return chunk_size >= 16 && chunk_size <=
 
 }  // namespace
 
+// Kernel shape by number of query rows per KV head.  Up to 32 rows the pass is purely HBM-bound
+// and the 16x16x32 kernel with its small workgroups (many of them per CU) is used; beyond that
+// the 32x32x16 kernel, in row tiles of at most 384 rows.
+bool ts::verify_shape(int n_rows, int variant, VerifyShape *out)
+{
+    if (n_rows < 1 || n_rows > TS_MAX_GROUP * TS_MAX_TREE) return false;
+    if (variant == 0 && n_rows <= 16) {
+        *out = VerifyShape{kNarrow_16, 16, 5};
+        return true;
+    }
+    if (variant == 0 && n_rows <= 32) {
+        *out = VerifyShape{kNarrow_32, 32, 4};
+        return true;
+    }
+    const int tiles = (n_rows + 383) / 384;
+    const int r = ((n_rows + tiles - 1) / tiles + 31) / 32 * 32;   // rows per tile, balanced
+    if (r <= 32) *out = VerifyShape{kWide_1x1, 32, 3};
+    else if (r <= 64) *out = VerifyShape{kWide_1x2, 64, 2};
+    else if (r <= 128) *out = VerifyShape{variant == 2 ? kWide_1x4p : kWide_1x4, 128, 2};
+    else if (r <= 256) *out = VerifyShape{variant == 2 ? kWide_1x8 : kWide_2x4, 256, 1};
+    else *out = VerifyShape{variant == 2 ? kWide_3x4 : kWide_3x4q, 384, 1};
+    out->rows_per_wg = r;
+    return true;
+}
+
 extern "C" {
 
 const char *ts_strerror(int status)
@@ -130,13 +154,8 @@ int ts_tune_set(const char *name, int value)
         g_tune.verify_splits = value;
         return TS_OK;
     }
-    if (strcmp(name, "verify_impl") == 0) {
-        if (value > 1) return TS_ERR_UNSUPPORTED;
-        g_tune.verify_impl = value;
-        return TS_OK;
-    }
     if (strcmp(name, "verify_variant") == 0) {
-        if (value > 4) return TS_ERR_UNSUPPORTED;
+        if (value > 2) return TS_ERR_UNSUPPORTED;
         g_tune.verify_variant = value;
         return TS_OK;
     }
@@ -304,14 +323,20 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
     p.n_tree = n_tree;
     p.n_rows = pl.n_rows;
     p.n_rows_pad = pl.n_rows_pad;
+    p.rows_per_wg = pl.shape.rows_per_wg;
     p.scale_log2 = scale * 1.4426950408889634f;
     // ancestor-or-self bit masks (App. E: a node attends only to its predecessors)
-    for (int i = 0; i < 64; ++i) p.anc[i] = 0;
-    for (int i = 0; i < n_tree; ++i)
-        p.anc[i] = (1ull << i) | (parent[i] >= 0 ? p.anc[parent[i]] : 0ull);
+    memset(p.anc, 0, sizeof(p.anc));
+    for (int i = 0; i < n_tree; ++i) {
+        if (parent[i] >= 0) {
+            p.anc[i][0] = p.anc[parent[i]][0];
+            p.anc[i][1] = p.anc[parent[i]][1];
+        }
+        p.anc[i][i >> 6] |= 1ull << (i & 63);
+    }
     if (g_tune.verify_stage != 2) {
-        const hipError_t e = g_tune.verify_impl == 1 ? ts::launch_verify(p, st)
-                                                     : ts::launch_verify_dma(p, st, g_tune.verify_variant);
+        const hipError_t e = pl.shape.kernel_id <= ts::kNarrow_32 ? ts::launch_verify_narrow(p, pl.shape.kernel_id, st)
+                                                                  : ts::launch_verify_wide(p, pl.shape.kernel_id, st);
         if (e != hipSuccess) return TS_ERR_HIP;
     }
     if (g_tune.verify_stage == 1) return TS_OK;

@@ -5,7 +5,8 @@
 
 namespace ts {
 
-// ---- tree verification (verify_kernel.hip) -------------------------------------------------
+// ---- tree verification (verify_dma_kernel.hip, verify_wide_kernel.hip) ----------------------
+constexpr int kMaxTree = 128;
 struct VerifyParams {
     const uint16_t *q;        // bf16 [n_tree][n_q_heads][128]
     const uint16_t *k;        // cache keys
@@ -19,14 +20,35 @@ struct VerifyParams {
     int64_t split_len;        // cached tokens per split, multiple of 32
     int n_split;              // number of cache splits (0 if the cache is empty); index n_split = tree
     int n_q_heads, n_kv_heads, group, n_tree;
-    int n_rows;               // group * n_tree
+    int n_rows;               // group * n_tree; row = node * group + head within the group
     int n_rows_pad;           // row pitch of the workspace
+    int rows_per_wg;          // query rows one workgroup covers (grid.z = ceil(n_rows / rows_per_wg))
     float scale_log2;         // scale * log2(e)
-    uint64_t anc[64];         // anc[i] bit u set iff tree node u is i or an ancestor of i
+    uint64_t anc[kMaxTree][2];   // bit u of the 128-bit anc[i] set iff tree node u is i or an ancestor of i
 };
-int verify_rows_capacity(int n_rows);   // 0 if too many rows
-hipError_t launch_verify(const VerifyParams &p, hipStream_t stream);        // K/V staged through registers
-hipError_t launch_verify_dma(const VerifyParams &p, hipStream_t stream, int variant);   // K/V loaded straight into LDS
+
+// Which kernel instantiation serves a number of query rows per KV head, and what the split
+// heuristic needs to know about it.
+enum VerifyKernelId {
+    kNarrow_16 = 0,   // 16x16x32 MFMA kernel, 1 wavefront x 16 rows
+    kNarrow_32,       // 16x16x32 MFMA kernel, 2 wavefronts x 16 rows
+    kWide_1x1,        // 32x32x16 MFMA kernel, NRB x WR: 32-row blocks per wavefront x wavefronts
+    kWide_1x2,
+    kWide_1x4,
+    kWide_1x4p,       // software-pipelined main loop
+    kWide_2x4,
+    kWide_1x8,
+    kWide_3x4,
+    kWide_3x4q,       // query fragments in LDS
+};
+struct VerifyShape {
+    int kernel_id;
+    int rows_per_wg;   // rows covered by one workgroup (multiple of 32 for the wide kernel)
+    int wg_per_cu;     // workgroups of this shape one CU holds at a time
+};
+bool verify_shape(int n_rows, int variant, VerifyShape *out);   // false if n_rows is out of range
+hipError_t launch_verify_narrow(const VerifyParams &p, int kernel_id, hipStream_t stream);
+hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t stream);
 
 // ---- partial-KV attention (partial_kernel.hip) ---------------------------------------------
 struct PartialParams {

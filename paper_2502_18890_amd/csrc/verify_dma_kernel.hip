@@ -2,11 +2,12 @@
 // App. E of the TokenSwift paper), split along the cache, for gfx950 -- variant whose K/V
 // tiles go from HBM straight into LDS (buffer_load ... lds), several tiles ahead of compute.
 //
-// Work decomposition and arithmetic are those of verify_kernel.hip: one workgroup = one KV
-// head x one contiguous range of cached tokens (last split index = the tree tokens with the
-// ancestor mask); S^T = K.Q^T and O^T += V^T.P^T on v_mfma_f32_16x16x32_bf16 with keys on the
-// M axis, online softmax in fp32 (exp2 domain), P as bf16 hi + lo.  What differs is the data
-// path.  A tile is 32 keys: 8 KiB of K and 8 KiB of V, unpadded.  Each wavefront load
+// This is the kernel for at most 32 query rows per KV head (MHA, narrow trees), where the pass
+// is purely HBM-bound.  One workgroup = one KV head x one contiguous range of cached tokens
+// (last split index = the tree tokens with the ancestor mask); S^T = K.Q^T and O^T += V^T.P^T
+// on v_mfma_f32_16x16x32_bf16 with keys on the M axis, so that all logits a lane owns belong
+// to one query row; online softmax in fp32 (exp2 domain), P as bf16 hi + lo.
+// A tile is 32 keys: 8 KiB of K and 8 KiB of V, unpadded.  Each wavefront load
 // instruction moves four whole 256-byte rows (64 lanes x 16 B) into 1 KiB of LDS without
 // touching a VGPR, so the bytes in flight are bounded by LDS (NS stages per workgroup), not
 // by registers; the pass is HBM-bound and wants as many bytes in flight as it can get.
@@ -35,6 +36,7 @@ constexpr int kTileKeys = 32;
 constexpr int kStageBytes = kTileKeys * 512;   // K half then V half
 constexpr int kVHalf = kTileKeys * 256;
 constexpr int kQRowBytes = 272;                // padded query rows (QLDS)
+constexpr float kRescaleSlack = 8.0f;          // log2 units
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
@@ -102,7 +104,7 @@ verify_dma_kernel(const VerifyParams p)
         const int node = live ? row / p.group : 0;
         const int jj = live ? row % p.group : 0;
         const uint16_t *qrow = p.q + ((int64_t)node * p.n_q_heads + h * p.group + jj) * kHeadDim;
-        amask[rb] = live ? p.anc[node] : 0ull;
+        amask[rb] = live ? p.anc[node][0] : 0ull;   // at most 32 rows here, so at most 32 tree nodes
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             u32x4 raw = {0u, 0u, 0u, 0u};
@@ -237,7 +239,10 @@ verify_dma_kernel(const VerifyParams p)
 
         // ---- (2) row maxima (raw logits; scale > 0 commutes with max) --------------------------
         // This lane owns keys kb*16 + quad*4 + v (e = kb*4 + v) of query row j.
-        float m_new[NRB];
+        // m_run is a reference point, not necessarily the exact running maximum: the accumulators
+        // are rescaled only when a tile's maximum exceeds it by more than kRescaleSlack, so the
+        // weights stay <= 2^kRescaleSlack and the (rare) rescale leaves the common path.
+        float m_tile[NRB];
         bool moved = false;
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
@@ -252,20 +257,20 @@ verify_dma_kernel(const VerifyParams p)
             }
             const f32x4 s0 = sacc[rb][0], s1 = sacc[rb][1];
             float mloc = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])), fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
-            mloc = xrow_max(mloc);
-            m_new[rb] = fmaxf(m_run[rb], mloc * p.scale_log2);
-            moved |= (m_new[rb] != m_run[rb]);
+            m_tile[rb] = xrow_max(mloc) * p.scale_log2;
+            moved |= (m_tile[rb] > m_run[rb] + kRescaleSlack);
         }
-        if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {   // some row of this wavefront saw a new maximum
+        if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {   // some row of this wavefront outgrew its reference
 #pragma unroll
             for (int rb = 0; rb < NRB; ++rb) {
-                const float alpha = fast_exp2(m_run[rb] - m_new[rb]);
+                const float m_new = fmaxf(m_run[rb], m_tile[rb]);
+                const float alpha = fast_exp2(m_run[rb] - m_new);
                 l_run[rb] *= alpha;
 #pragma unroll
                 for (int dg = 0; dg < 2; ++dg)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) oacc[rb][dg][i] *= alpha;
-                m_run[rb] = m_new[rb];
+                m_run[rb] = m_new;
             }
         }
 
@@ -369,41 +374,11 @@ hipError_t launch_one(const VerifyParams &p, hipStream_t stream)
 
 }  // namespace
 
-hipError_t launch_verify_dma(const VerifyParams &p, hipStream_t stream, int variant)
+hipError_t launch_verify_narrow(const VerifyParams &p, int kernel_id, hipStream_t stream)
 {
-    switch (verify_rows_capacity(p.n_rows)) {
-        case 16: return launch_one<1, 1, 2, 2, false>(p, stream);
-        case 32:
-            switch (variant) {
-                case 1: return launch_one<1, 2, 3, 2, false>(p, stream);
-                case 2: return launch_one<1, 2, 4, 2, false>(p, stream);
-                case 3: return launch_one<2, 1, 2, 2, false>(p, stream);
-                case 4: return launch_one<2, 1, 4, 2, false>(p, stream);
-                default: return launch_one<1, 2, 2, 2, false>(p, stream);   // 4 workgroups per CU
-            }
-        case 64: return launch_one<2, 2, 3, 2, false>(p, stream);
-        case 96: return launch_one<3, 2, 4, 1, false>(p, stream);
-        case 128:
-            switch (variant) {
-                case 1: return launch_one<2, 4, 4, 2, false>(p, stream);
-                case 2: return launch_one<2, 4, 8, 2, false>(p, stream);
-                case 3: return launch_one<4, 2, 4, 1, false>(p, stream);
-                case 4: return launch_one<1, 8, 2, 4, false>(p, stream);
-                default: return launch_one<2, 4, 2, 2, false>(p, stream);
-            }
-        case 192: return launch_one<3, 4, 8, 1, false>(p, stream);
-        case 256: return launch_one<4, 4, 8, 1, false>(p, stream);
-        case 320:
-            switch (variant) {
-                case 1: return launch_one<3, 8, 3, 2, true>(p, stream);
-                default: return launch_one<5, 4, 4, 1, true>(p, stream);
-            }
-        case 384:
-            switch (variant) {
-                case 1: return launch_one<3, 8, 3, 2, true>(p, stream);
-                default: return launch_one<6, 4, 3, 1, true>(p, stream);
-            }
-        case 512: return launch_one<4, 4, 8, 1, false>(p, stream);
+    switch (kernel_id) {
+        case kNarrow_16: return launch_one<1, 1, 2, 2, false>(p, stream);
+        case kNarrow_32: return launch_one<1, 2, 2, 2, false>(p, stream);   // 4 workgroups per CU
         default: return hipErrorInvalidValue;
     }
 }

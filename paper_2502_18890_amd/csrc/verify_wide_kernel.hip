@@ -1,0 +1,474 @@
+// Tree-masked verification attention over the full KV cache (Alg. 1 "Parallel Verification",
+// App. E of the TokenSwift paper), split along the cache, for gfx950 -- the kernel for more than
+// 32 query rows per KV head (GQA groups, wide trees), built on v_mfma_f32_32x32x16_bf16.
+//
+// On this part the 32x32x16 instruction delivers twice the flops per issue slot of 16x16x32,
+// and once g*T reaches ~100 rows the pass is no longer purely HBM-bound: the matrix and vector
+// units have to be kept busy at the same time.  Work decomposition: one workgroup = one KV
+// head x one contiguous range of cached tokens (split index n_split = the tree tokens with the
+// ancestor mask) x up to 32*NRB*WR query rows; 32-row blocks are dealt round-robin to the WR
+// wavefronts, every wavefront applies each 32-key tile to its own blocks.
+//
+//   S^T = K . Q^T    A = K tile  (32 keys x 16 dims),   B = Q^T (16 dims x 32 rows), 8 steps
+//   O^T += V^T . P^T A = V^T     (32 cols x 16 keys),   B = P^T (16 keys x 32 rows), 2 steps x 4 column blocks
+//
+// Keys sit on the MFMA M axis, so the 16 logits a lane owns all belong to one query row (lane
+// mod 32): running max and sum are per-lane state, the row max needs one v_permlane32_swap, and
+// the probabilities a lane computes are exactly the B-operand elements it must supply for the
+// second product (the contraction order of keys is permuted the same way on the V^T side).
+// The V^T operand needs 8 keys of one column per lane: a lane reads 4 consecutive columns of
+// each of its 16 keys (ds_read_b64) and regroups them with v_perm_b32 into the operands of 4
+// column blocks; column block c then holds columns 4m+c, so a lane ends up with runs of 4
+// consecutive output columns and writes its partial with 128-bit stores.
+// P is split into hi + lo (both bf16) and multiplied twice, which keeps ~16 bits per weight.
+//
+// Data path: buffer_load_dwordx4 ... lds moves four 256-byte rows per instruction from HBM
+// straight into an NS-stage LDS ring (no VGPR staging); 16-byte pieces are permuted on the way
+// in so that operand reads are bank-conflict free:
+//   K rows: LDS piece pos of row R holds global piece pos ^ (R mod 16);
+//   V rows: LDS piece pos of row R holds global piece pos ^ 8*((R/4) mod 2).
+// Rows past the end of a range are cut off by the buffer descriptor's byte count; the ring is
+// cleared once so a stage never holds anything but finite values (a masked key adds 0 * V).
+#include <type_traits>
+
+#include "ts_device.hpp"
+#include "ts_internal.hpp"
+
+namespace ts {
+
+namespace {
+
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kTileKeys = 32;
+constexpr int kStageBytes = kTileKeys * 512;   // K half then V half
+constexpr int kVHalf = kTileKeys * 256;
+constexpr int kQRowBytes = 272;                // padded query rows (QLDS)
+constexpr float kRescaleSlack = 8.0f;          // log2 units
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ float swap32_max(float x)
+{
+    u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float swap32_sum(float x)
+{
+    u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// NRB: 32-row blocks per wavefront; WR: wavefronts per workgroup; NS: LDS stages (NS-2 tiles in
+// flight while two are resident); OCC: wavefronts per SIMD the register budget is cut for;
+// QLDS: query fragments live in LDS instead of registers.
+template <int NRB, int WR, int NS, int OCC, bool QLDS, bool PIPE>
+__global__ void __launch_bounds__(64 * WR) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
+verify_wide_kernel(const VerifyParams p)
+{
+    constexpr int NT = 64 * WR;
+    constexpr int LPW = 16 / WR;   // load instructions per wavefront per tile (16 x 1 KiB = one tile)
+    constexpr int RES = PIPE ? 2 : 1;   // tiles resident in LDS while the others are in flight
+    static_assert(16 % WR == 0 && NS >= RES + 1, "bad shape");
+    static_assert((NS - RES - 1) * LPW <= 63, "too many loads in flight for vmcnt");
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n32 = lane & 31;     // query row within a 32-row block / key row of a K operand
+    const int hh = lane >> 5;      // which half of the contraction slice this lane supplies
+    const int j = lane & 15;       // 16-byte piece a lane moves in a tile load
+    const int quad = lane >> 4;
+    const int split = blockIdx.x;
+    const int h = blockIdx.y;
+    const bool is_tree = (split == p.n_split);
+
+    const uint16_t *kbase, *vbase;
+    int64_t tstride, t_begin, t_end;
+    if (is_tree) {
+        kbase = p.k_tree + (int64_t)h * kHeadDim;
+        vbase = p.v_tree + (int64_t)h * kHeadDim;
+        tstride = (int64_t)p.n_kv_heads * kHeadDim;
+        t_begin = 0;
+        t_end = p.n_tree;
+    } else {
+        kbase = p.k + (int64_t)h * p.stride_head;
+        vbase = p.v + (int64_t)h * p.stride_head;
+        tstride = p.stride_token;
+        t_begin = (int64_t)split * p.split_len;
+        t_end = t_begin + p.split_len < p.n_tokens ? t_begin + p.split_len : p.n_tokens;
+    }
+
+    // ---- clear the ring --------------------------------------------------------------------
+    {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int off = tid * 16; off < NS * kStageBytes; off += NT * 16) *reinterpret_cast<u32x4 *>(lds + off) = z;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS traffic only
+
+    // ---- rows of this wavefront: 32-row blocks wave, wave + WR, ... of the workgroup's row tile ----
+    const int tile_row0 = blockIdx.z * p.rows_per_wg;
+    const int tile_rows = (p.n_rows - tile_row0) < p.rows_per_wg ? (p.n_rows - tile_row0) : p.rows_per_wg;
+    // number of live blocks of this wavefront (wave-uniform)
+    const int n_blocks = (tile_rows + 31) >> 5;
+    const int nrb_live = __builtin_amdgcn_readfirstlane(n_blocks > wave ? (n_blocks - wave + WR - 1) / WR : 0);
+
+    // ---- query fragments (MFMA B operand): loads issued now, awaited after the prefetch is out --
+    unsigned char *qlds = lds + NS * kStageBytes + (wave * NRB * 32) * kQRowBytes;
+    u32x4 qraw[NRB][8];
+    uint64_t amask_lo[NRB], amask_hi[NRB];   // ancestor-or-self bits of tree nodes 0..63 and 64..127
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        const int row = tile_row0 + (rb * WR + wave) * 32 + n32;
+        const bool live = rb < nrb_live && row < p.n_rows;
+        const int node = live ? row / p.group : 0;
+        const int jj = live ? row % p.group : 0;
+        const uint16_t *qrow = p.q + ((int64_t)node * p.n_q_heads + h * p.group + jj) * kHeadDim;
+        amask_lo[rb] = live ? p.anc[node][0] : 0ull;
+        amask_hi[rb] = live ? p.anc[node][1] : 0ull;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (live) raw = *reinterpret_cast<const u32x4 *>(qrow + ks * 16 + hh * 8);
+            qraw[rb][ks] = raw;
+        }
+    }
+
+    float m_run[NRB], l_run[NRB];
+    f32x16 oacc[NRB][4];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        m_run[rb] = kNegBig;
+        l_run[rb] = 0.f;
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[rb][cb][e] = 0.f;
+    }
+
+    // ---- HBM -> LDS -------------------------------------------------------------------------
+    // Load instruction ii (0..15) of a tile fills LDS block ii: K rows 4ii..4ii+3 for ii < 8,
+    // V rows 4(ii-8).. for ii >= 8.  This wavefront issues ii = wave*LPW .. wave*LPW+LPW-1.
+    uint32_t goff[LPW];
+#pragma unroll
+    for (int i = 0; i < LPW; ++i) {
+        const int ii = wave * LPW + i;
+        const int R = 4 * (ii & 7) + quad;                       // row of the tile this lane fetches from
+        const int f = (ii >= 8) ? (((R >> 2) & 1) << 3) : (R & 15);
+        goff[i] = (uint32_t)(R * tstride * 2 + ((j ^ f) << 4));
+    }
+    auto issue_tile = [&](int64_t tile) {
+        const int64_t t0 = t_begin + tile * kTileKeys;
+        const int64_t span = t0 < t_end ? (t_end - t0 - 1) * tstride * 2 + 256 : 0;   // bytes up to the end of the last valid row
+        const uint32_t nrec = span > 0xffffffffLL ? 0xffffffffu : (uint32_t)span;
+        const int64_t tb = t0 < t_end ? t0 : t_begin;            // keep the base inside the allocation
+        const __amdgpu_buffer_rsrc_t rk =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(kbase + tb * tstride), 0, nrec, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rv =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(vbase + tb * tstride), 0, nrec, 0x00020000);
+        unsigned char *stage = lds + (int)(tile % NS) * kStageBytes;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const int ii = wave * LPW + i;                       // wave-uniform
+            const uint32_t go = goff[i];
+            if (ii < 8)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void_ptr)(stage + ii * 1024), 16, go, 0, 0, 0);
+            else
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void_ptr)(stage + kVHalf + (ii - 8) * 1024), 16, go, 0, 0, 0);
+        }
+    };
+
+    // per-lane LDS read offsets inside a stage
+    int koff[8];   // K operand of step ks: key row n32, global piece 2ks+hh
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) koff[ks] = n32 * 256 + ((((ks << 1) | hh) ^ (n32 & 15)) << 4);
+    // V: this lane's keys are hh*4 + 8i + v (i, v = 0..3); it reads columns 4*n32 .. 4*n32+3 of each
+    const int voff = kVHalf + hh * 1024 + ((((n32 >> 1)) ^ (hh << 3)) << 4) + ((n32 & 1) << 3);
+
+    const int64_t n_tiles = (t_end - t_begin + kTileKeys - 1) / kTileKeys;
+#pragma unroll
+    for (int s = 0; s < NS - RES; ++s) issue_tile(s);   // tiles past the range load nothing but still count
+
+    // Now wait for the query and mask loads (older than every tile load, so the tile loads stay
+    // in flight) -- here, not at their first use inside the main loop, where the wait would be
+    // for everything issued before it, i.e. for the whole prefetched ring.
+    bf16x8 qf[QLDS ? 1 : NRB][8];
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        asm volatile("" ::"v"(amask_lo[rb]), "v"(amask_hi[rb]));
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            asm volatile("" ::"v"(qraw[rb][ks]));
+            if (QLDS)   // each wavefront later reads back only what it wrote itself
+                *reinterpret_cast<u32x4 *>(qlds + (rb * 32 + n32) * kQRowBytes + (ks * 16 + hh * 8) * 2) = qraw[rb][ks];
+            else
+                qf[rb][ks] = __builtin_bit_cast(bf16x8, qraw[rb][ks]);
+        }
+    }
+
+    // One 32-key tile against all of this wavefront's row blocks.  RAGGED tiles (the last one of
+    // a range, every tile of the tree split) mask keys; full tiles carry no masking code.
+    // The tile body comes in two pieces so that the main loop can be software-pipelined: the
+    // matrix work S^T(tile t+1) is independent of the vector work softmax(tile t), and issuing it
+    // first lets one wavefront keep both units busy.  L = number of row blocks computed (compile
+    // time, so that the body is straight-line code the scheduler can interleave freely); a block
+    // beyond the wavefront's live ones holds zero queries and is never written back.
+
+    // ---- S^T = K . Q^T of one tile --------------------------------------------------------------
+    auto qk_tile = [&](auto live_tag, const unsigned char *stage, auto &sacc) {
+        constexpr int L = decltype(live_tag)::value;
+#pragma unroll
+        for (int rb = 0; rb < L; ++rb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sacc[rb][e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(stage + koff[ks]);
+#pragma unroll
+            for (int rb = 0; rb < L; ++rb) {
+                const bf16x8 b = QLDS ? *reinterpret_cast<const bf16x8 *>(
+                                            qlds + (rb * 32 + n32) * kQRowBytes + (ks * 16 + hh * 8) * 2)
+                                      : qf[QLDS ? 0 : rb][ks];
+                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, sacc[rb], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- softmax of one tile's logits and O^T += V^T . P^T ----------------------------------------
+    // RAGGED tiles (the last one of a range, every tile of the tree split) mask keys; full tiles
+    // carry no masking code.
+    auto pv_tile = [&](auto live_tag, auto ragged_tag, const unsigned char *stage, int64_t t0, auto &sacc) {
+        constexpr int L = decltype(live_tag)::value;
+        constexpr bool RAGGED = decltype(ragged_tag)::value;
+
+        // V^T operands: vt[cb][s] = column 4*n32+cb, keys hh*4 + 8*(2s + e/4) + e%4 (e = 0..7)
+        bf16x8 vt[4][2];
+        {
+            u32x2 vr[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                vr[e] = *reinterpret_cast<const u32x2 *>(stage + voff + (8 * (e >> 2) + (e & 3)) * 256);
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    u32x4 a;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        const uint32_t x = vr[8 * s + 2 * w][cb >> 1], y = vr[8 * s + 2 * w + 1][cb >> 1];
+                        a[w] = (cb & 1) ? __builtin_amdgcn_perm(y, x, 0x07060302u) : __builtin_amdgcn_perm(y, x, 0x05040100u);
+                    }
+                    vt[cb][s] = __builtin_bit_cast(bf16x8, a);
+                }
+        }
+
+        // Row maxima (raw logits; scale > 0 commutes with max).  Element e of sacc is key
+        // hh*4 + 8*(e/4) + e%4 of the tile, for query row n32.  m_run is a reference point, not
+        // necessarily the exact running maximum: the accumulators are rescaled only when a tile's
+        // maximum exceeds it by more than kRescaleSlack, so the weights stay <= 2^kRescaleSlack and
+        // the (rare) rescale leaves the common path.
+        float m_tile[L > 0 ? L : 1];
+        bool moved = false;
+#pragma unroll
+        for (int rb = 0; rb < L; ++rb) {
+            if (RAGGED) {
+                uint64_t tile_ok;
+                if (is_tree) {
+                    const uint64_t w = (t0 & 64) ? amask_hi[rb] : amask_lo[rb];
+                    tile_ok = w >> (t0 & 63);
+                } else {
+                    tile_ok = t_end - t0 >= 64 ? ~0ull : ((1ull << (t_end - t0)) - 1ull);
+                }
+                const uint32_t vm = (uint32_t)tile_ok >> (hh * 4);
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    if (!((vm >> (8 * (e >> 2) + (e & 3))) & 1u)) sacc[rb][e] = -INFINITY;
+            }
+            float mloc = sacc[rb][0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e) mloc = fmaxf(mloc, sacc[rb][e]);
+            m_tile[rb] = swap32_max(mloc) * p.scale_log2;
+            moved |= (m_tile[rb] > m_run[rb] + kRescaleSlack);
+        }
+        if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {   // some row of this wavefront outgrew its reference
+#pragma unroll
+            for (int rb = 0; rb < L; ++rb) {
+                const float m_new = fmaxf(m_run[rb], m_tile[rb]);
+                const float alpha = fast_exp2(m_run[rb] - m_new);
+                l_run[rb] *= alpha;
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) oacc[rb][cb][e] *= alpha;
+                m_run[rb] = m_new;
+            }
+        }
+
+        // P = exp2(scale*s - m), split hi + lo (both bf16), O^T += V^T . P^T
+#pragma unroll
+        for (int rb = 0; rb < L; ++rb) {
+            float pe[16], psum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                pe[e] = fast_exp2(fmaf(sacc[rb][e], p.scale_log2, -m_run[rb]));
+                psum += pe[e];
+            }
+            l_run[rb] += psum;
+            bf16x8 p_hi[2], p_lo[2];
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                u32x4 hi, lo;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float a = pe[8 * s + 2 * w], b = pe[8 * s + 2 * w + 1];
+                    const uint32_t hw = pack_bf16(a, b);
+                    hi[w] = hw;
+                    lo[w] = pack_bf16(a - bf16lo_to_f32(hw), b - bf16hi_to_f32(hw));
+                }
+                p_hi[s] = __builtin_bit_cast(bf16x8, hi);
+                p_lo[s] = __builtin_bit_cast(bf16x8, lo);
+            }
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb) {
+                    oacc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[cb][s], p_hi[s], oacc[rb][cb], 0, 0, 0);
+                    oacc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[cb][s], p_lo[s], oacc[rb][cb], 0, 0, 0);
+                }
+        }
+    };
+
+    // Main loop.  Tile t lives in stage t % NS.  Plain form: one tile resident, NS-1 in flight.
+    // Pipelined form: step `it` needs the keys of tile it+1 and the values of tile it, so two
+    // tiles are resident and NS-2 in flight.  Every wavefront of the workgroup runs the same
+    // number of steps (one barrier each), whichever instantiation of the body it takes.
+    const int64_t n_full = is_tree ? 0 : (t_end - t_begin) / kTileKeys;
+    auto sync_and_refill = [&](int64_t landed_tile) {
+        // this wavefront's pieces of `landed_tile` have landed: the NS-RES-1 tiles issued after it
+        // may still be in flight
+        wait_vmcnt<(NS - RES - 1) * LPW>();
+        // ... and everyone's; all are done with tile landed_tile-RES.  A bare s_barrier: __syncthreads()
+        // would add a fence that waits for every outstanding load, i.e. for the whole prefetched ring.
+        if (WR > 1) asm volatile("s_barrier" ::: "memory");
+        issue_tile(landed_tile + NS - RES);           // refills the stage that tile landed_tile-RES occupied
+    };
+    auto run = [&](auto live_tag) {
+        constexpr int L = decltype(live_tag)::value;
+        f32x16 s_cur[L > 0 ? L : 1];
+        if (!PIPE) {
+            // full tiles first, then (cache ranges) at most one ragged tile; the tree split is all ragged
+            auto step = [&](auto ragged_tag, int64_t it) {
+                sync_and_refill(it);
+                if (L > 0) {
+                    const unsigned char *stage = lds + (int)(it % NS) * kStageBytes;
+                    qk_tile(live_tag, stage, s_cur);
+                    pv_tile(live_tag, ragged_tag, stage, t_begin + it * kTileKeys, s_cur);
+                }
+            };
+            for (int64_t it = 0; it < n_full; ++it) step(std::false_type{}, it);
+            for (int64_t it = n_full; it < n_tiles; ++it) step(std::true_type{}, it);
+            return;
+        }
+        // Pipelined: S^T of tile it+1 is issued before the softmax of tile it.  The steady state is
+        // unrolled twice so that the two logit buffers swap roles without copies.
+        f32x16 s_nxt[L > 0 ? L : 1];
+        auto stage_of = [&](int64_t t) { return lds + (int)(t % NS) * kStageBytes; };
+        sync_and_refill(0);   // prologue: tile 0
+        if (L > 0) qk_tile(live_tag, stage_of(0), s_cur);
+        int64_t it = 0;
+        for (; it + 2 < n_full; it += 2) {   // tiles it, it+1 full; tiles it+1, it+2 exist
+            sync_and_refill(it + 1);
+            if (L > 0) {
+                qk_tile(live_tag, stage_of(it + 1), s_nxt);
+                pv_tile(live_tag, std::false_type{}, stage_of(it), t_begin + it * kTileKeys, s_cur);
+            }
+            sync_and_refill(it + 2);
+            if (L > 0) {
+                qk_tile(live_tag, stage_of(it + 2), s_cur);
+                pv_tile(live_tag, std::false_type{}, stage_of(it + 1), t_begin + (it + 1) * kTileKeys, s_nxt);
+            }
+        }
+        for (; it < n_tiles; ++it) {         // the last few tiles, ragged ones included
+            sync_and_refill(it + 1);
+            if (L > 0) {
+                if (it + 1 < n_tiles) qk_tile(live_tag, stage_of(it + 1), s_nxt);
+                if (it < n_full) pv_tile(live_tag, std::false_type{}, stage_of(it), t_begin + it * kTileKeys, s_cur);
+                else pv_tile(live_tag, std::true_type{}, stage_of(it), t_begin + it * kTileKeys, s_cur);
+#pragma unroll
+                for (int rb = 0; rb < L; ++rb) s_cur[rb] = s_nxt[rb];
+            }
+        }
+    };
+    if (nrb_live == NRB) run(std::integral_constant<int, NRB>{});
+    else run(std::integral_constant<int, NRB - 1>{});   // round-robin dealing: never fewer than NRB-1 unless none at all
+    wait_vmcnt<0>();   // drain the loads issued past the range before the workgroup's LDS is released
+
+    // ---- write the partial: (m, l) and unnormalised O for every live row ----------------------
+    const int n_part = p.n_split + 1;
+    const int64_t part = ((int64_t)h * n_part + split) * p.n_rows_pad;
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb) {
+        if (rb < nrb_live) {
+            const int row = tile_row0 + (rb * WR + wave) * 32 + n32;
+            const float l_tot = swap32_sum(l_run[rb]);
+            if (row < p.n_rows) {
+                if (hh == 0) {
+                    f32x2 ml = {m_run[rb], l_tot};
+                    *reinterpret_cast<f32x2 *>(p.ws_ml + (part + row) * 2) = ml;
+                }
+                float *orow = p.ws_o + (part + row) * kHeadDim;
+                // element e of oacc[rb][cb] is output column 4*(hh*4 + 8*(e/4) + e%4) + cb
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    f32x4 o = {oacc[rb][0][e], oacc[rb][1][e], oacc[rb][2][e], oacc[rb][3][e]};
+                    *reinterpret_cast<f32x4 *>(orow + 4 * (hh * 4 + 8 * (e >> 2) + (e & 3))) = o;
+                }
+            }
+        }
+    }
+}
+
+template <int NRB, int WR, int NS, int OCC, bool QLDS, bool PIPE = false>
+hipError_t launch_one(const VerifyParams &p, hipStream_t stream)
+{
+    constexpr int kRows = 32 * NRB * WR;
+    constexpr int lds_bytes = NS * kStageBytes + (QLDS ? kRows * kQRowBytes : 0);
+    static_assert(lds_bytes <= 160 * 1024, "LDS budget");
+    if (p.rows_per_wg > kRows || p.rows_per_wg % 32 != 0) return hipErrorInvalidValue;
+    static bool attr_set = false;
+    if (lds_bytes > 64 * 1024 && !attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(verify_wide_kernel<NRB, WR, NS, OCC, QLDS, PIPE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid(p.n_split + 1, p.n_kv_heads, (p.n_rows + p.rows_per_wg - 1) / p.rows_per_wg);
+    hipLaunchKernelGGL((verify_wide_kernel<NRB, WR, NS, OCC, QLDS, PIPE>), grid, dim3(64 * WR), lds_bytes, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t stream)
+{
+    switch (kernel_id) {
+        case kWide_1x1: return launch_one<1, 1, 3, 2, false>(p, stream);
+        case kWide_1x2: return launch_one<1, 2, 4, 2, false>(p, stream);
+        case kWide_1x4: return launch_one<1, 4, 4, 2, false>(p, stream);
+        case kWide_1x4p: return launch_one<1, 4, 4, 2, false, true>(p, stream);
+        case kWide_2x4: return launch_one<2, 4, 6, 1, false>(p, stream);
+        case kWide_1x8: return launch_one<1, 8, 6, 2, false>(p, stream);
+        case kWide_3x4: return launch_one<3, 4, 6, 1, false>(p, stream);
+        case kWide_3x4q: return launch_one<3, 4, 3, 1, true>(p, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace ts

@@ -53,7 +53,7 @@ def test_workspace_bytes(binding):
     assert wb(V, 32, 32, 100000, 32) > 0
     assert wb(V, 32, 32, 0, 32) > 0                       # empty cache: tree partial only
     assert wb(V, 32, 32, 100000, 0) == 0                  # no tree
-    assert wb(V, 32, 32, 100000, 65) == 0                 # tree too large
+    assert wb(V, 32, 32, 100000, 129) == 0                # tree too large
     assert wb(V, 30, 8, 1000, 8) == 0                     # heads do not divide
     assert wb(V, 72, 8, 1000, 8) == 0                     # group 9 > 8
     assert wb(P, 32, 8, 65536, 0, 65, 64) >= 8 * 17 * 4 * (128 + 2) * 4   # one partial per 16 segments of 16 tokens
@@ -124,7 +124,7 @@ def test_attention_calls_reject_bad_arguments(lib, binding):
     assert tv([-1, 0, 3]) == TS_ERR_TREE
     assert tv([-2, 0]) == TS_ERR_TREE
     assert tv([]) == TS_ERR_SHAPE
-    assert tv([-1] * 65) == TS_ERR_UNSUPPORTED
+    assert tv([-1] * 129) == TS_ERR_UNSUPPORTED
     assert tv([-1, 0], hq=3) == TS_ERR_SHAPE
     assert tv([-1, 0], ws_=None) == TS_ERR_WORKSPACE and tv([-1, 0], wsb=100) == TS_ERR_WORKSPACE
     assert tv([-1, 0], view=_view(binding, d=96)) == TS_ERR_UNSUPPORTED

@@ -181,6 +181,7 @@ def test_verify_configs(ts, ci):
     (4, 1, 0, 8), (4, 1, 1, 1), (4, 4, 31, 5), (8, 2, 32, 16), (8, 2, 33, 16), (6, 1, 63, 7), (5, 1, 64, 13),
     (12, 2, 65, 16), (32, 8, 4096 + 17, 32), (32, 32, 1000, 32), (40, 8, 2100, 64), (6, 1, 500, 64),
     (8, 1, 300, 64), (8, 1, 700, 33), (16, 2, 257, 20), (7, 1, 129, 3), (2, 2, 97, 64), (3, 3, 5000, 2),
+    (8, 1, 100, 128), (32, 4, 64, 128), (5, 5, 1, 65), (1, 1, 40, 127), (24, 8, 350, 70),
 ])
 def test_verify_shapes(ts, hq, hkv, n, t):
     c = _case(7, hq, hkv, n, t)
@@ -250,20 +251,42 @@ def test_verify_split_override_and_determinism(ts):
         ts.tune_set("verify_splits", 0)
 
 
-@pytest.mark.parametrize("impl,variant", [(1, 0), (0, 0), (0, 1), (0, 2), (0, 3), (0, 4)])
+@pytest.mark.parametrize("variant", [0, 1, 2])
 @pytest.mark.parametrize("hq,hkv,n,t", [(8, 2, 1000, 8), (32, 8, 2085, 32), (12, 2, 999, 16), (40, 8, 700, 64),
-                                        (4, 4, 130, 3), (48, 8, 333, 64), (64, 8, 200, 64)])
-def test_verify_kernel_variants(ts, impl, variant, hq, hkv, n, t):
-    """Both data paths of the verification kernel (register-staged and direct-to-LDS) and the
-    alternative workgroup shapes must all match the oracle."""
+                                        (4, 4, 130, 3), (48, 8, 333, 64), (64, 8, 200, 64), (2, 2, 300, 32),
+                                        (16, 2, 450, 25), (4, 4, 97, 128), (32, 8, 260, 100), (16, 2, 129, 128)])
+def test_verify_kernel_variants(ts, variant, hq, hkv, n, t):
+    """Every kernel shape (the 16x16x32 kernel for few rows, the 32x32x16 kernel in its
+    alternative workgroup shapes, row tiles for more than 384 rows) must match the oracle."""
     c = _case(21, hq, hkv, n, t)
     parent = _random_parent(c["rng"], t)
     try:
-        ts.tune_set("verify_impl", impl)
         ts.tune_set("verify_variant", variant)
         out, lse, ref, rlse = _verify_both(ts, c, parent)
     finally:
-        ts.tune_set("verify_impl", 0)
         ts.tune_set("verify_variant", 0)
-    assert_close(out, ref, "verify out impl=%d variant=%d" % (impl, variant))
-    assert_close(lse, rlse, "verify lse impl=%d variant=%d" % (impl, variant))
+    assert_close(out, ref, "verify out variant=%d" % variant)
+    assert_close(lse, rlse, "verify lse variant=%d" % variant)
+
+
+@pytest.mark.parametrize("kind", ["chain", "star", "deep-wide"])
+def test_verify_wide_trees(ts, kind):
+    """Trees of more than 64 nodes (the paper's 40-node tree plus up to 60 retrieved n-gram
+    tokens): ancestor masks span both 64-bit words."""
+    t = 100
+    c = _case(22, 8, 2, 777, t)
+    if kind == "chain":
+        parent = np.arange(-1, t - 1, dtype=np.int32)
+    elif kind == "star":
+        parent = np.zeros(t, dtype=np.int32)
+        parent[0] = -1
+    else:   # 40-node [1,3,3,3] tree, then 20 chains of 3 hanging off the root
+        parent = [-1] + [0] * 3 + [1 + i // 3 for i in range(9)] + [4 + i // 3 for i in range(27)]
+        for _ in range(20):
+            b = len(parent)
+            parent += [0, b, b + 1]
+        parent = np.asarray(parent, dtype=np.int32)
+        assert len(parent) == t
+    out, lse, ref, rlse = _verify_both(ts, c, parent)
+    assert_close(out, ref, "verify out wide tree " + kind)
+    assert_close(lse, rlse, "verify lse wide tree " + kind)
