@@ -151,6 +151,31 @@ def main():
     parts = {name: timed(sweep(fn), reps) * 1e3 / n_layers
              for name, fn in (("scores", do_scores), ("topk", do_topk), ("partial", do_partial), ("verify", do_verify))}
 
+    # cache-maintenance calls around the path (not part of `value`): incremental key sums make
+    # the scoring pass read n_chunks*128 floats instead of every key
+    ksum = [ts.chunk_key_sums(x["k"], cfg.chunk) for x in layers]
+    kg, vg = ts.gather_chunks(layers[0]["k"], layers[0]["v"], idx, cfg.chunk)
+    acc = list(range(min(4, t)))
+    extras = {
+        "scores_from_key_sums": lambda i, x: ts.chunk_scores_from_sums(ksum[i], n, x["q"], cfg.chunk, cfg.scale, out=scores),
+        "key_sums_full_rebuild": lambda i, x: ts.chunk_key_sums(x["k"], cfg.chunk, out=ksum[i]),
+        "key_sums_last_chunk": lambda i, x: ts.chunk_key_sums(x["k"], cfg.chunk, out=ksum[i], chunk_begin=cfg.n_chunks - 1),
+        "append_accepted_4": lambda i, x: ts.append_accepted(x["k"], x["v"], n - len(acc), x["k_tree"], x["v_tree"], acc),
+        "chunk_list_admit_1": lambda i, x: ts.chunk_list_admit(idx, cfg.n_sink, cfg.n_chunks - 1, 1),
+        "gather_chunks": lambda i, x: ts.gather_chunks(x["k"], x["v"], idx, cfg.chunk),
+    }
+    do_topk(layers[0])
+    maint = {}
+    for name, fn in extras.items():
+        if name == "append_accepted_4":
+            saved = [(x["k"][:, n - len(acc):].clone(), x["v"][:, n - len(acc):].clone()) for x in layers]
+        maint[name] = timed(lambda: [fn(i, x) for i, x in enumerate(layers)], reps) * 1e3 / n_layers
+        if name == "append_accepted_4":      # put the overwritten cache rows back
+            for x, (sk, sv) in zip(layers, saved):
+                x["k"][:, n - len(acc):] = sk
+                x["v"][:, n - len(acc):] = sv
+    del kg, vg, ksum
+
     # the dominant kernel alone (split kernel of the verification pass), for the roofline
     ts.tune_set("verify_stage", 1)
     try:
@@ -173,6 +198,7 @@ def main():
             "layers": n_layers, "n_tokens": n},
         "breakdown_us_per_layer": {k: round(v, 3) for k, v in parts.items()},
         "verify_plus_partial_us_per_layer": round(parts["verify"] + parts["partial"], 3),
+        "cache_maintenance_us_per_layer": {k: round(v, 3) for k, v in maint.items()},
         "verify_call_gbs": round(alg_bytes / (parts["verify"] * 1e-6) / 1e9, 1),
         "wall_s_timed_region": round(wall, 3),
         "roofline": {"kernel": "verify_dma_kernel (split-K tree-verify attention, split kernel)", "bound": "hbm",

@@ -152,11 +152,81 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
                         int n_tree, float scale, float *out, float *lse, void *workspace,
                         size_t workspace_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Cache maintenance around the attention calls (Alg. 1: "update C_full", "Evict C_p",
+ * "Dynamic KV Cache Update"; Sec. 3.3 "Dynamic KV Cache Updates").
+ * ------------------------------------------------------------------------------------- */
+
+/*
+ * Appends the accepted draft tokens to the full cache (Alg. 1, last step of the loop: "update
+ * C_full"): for i < n_accepted, row kv->n_tokens + i of every KV head becomes the key/value
+ * of tree node accepted[i].
+ *   kv        the cache BEFORE the append (n_tokens = N); its k and v buffers are written and
+ *             must have room for N + n_accepted tokens per head (capacity is the caller's)
+ *   k_tree, v_tree  bf16 [n_tree][n_kv_heads][128]
+ *   accepted  HOST pointer, int32 [n_accepted], each in [0, n_tree): the accepted path
+ * n_tree, n_accepted: 1..TS_MAX_TREE.  kv->n_tokens may be 0.  The caller then uses N + n_accepted.
+ * Errors: TS_ERR_TREE for an index outside [0, n_tree); the others as above.
+ */
+int ts_append_accepted(const ts_kv_view *kv, const void *k_tree, const void *v_tree, int n_tree,
+                       const int32_t *accepted, int n_accepted, void *stream);
+
+/*
+ * When the partial cache must be rebuilt (Alg. 1, "if (|C_full| - e) > |B| - |S|"; Sec. 3.3:
+ * new tokens replace the least important entries of C_p from position |B|-1 towards |S|, and
+ * once they would pass |S| the importance scores are recomputed).  All sizes in tokens.
+ * Returns 1 if a rebuild is due, 0 if not, TS_ERR_SHAPE for negative or inconsistent sizes.
+ * Pure host arithmetic.
+ */
+int ts_refresh_due(int64_t n_tokens, int64_t n_tokens_at_refresh, int64_t budget_tokens, int64_t sink_tokens);
+
+/*
+ * Between rebuilds, newly generated tokens take the place of the least important entries of
+ * C_p, from its last position towards the sink (Sec. 3.3).  At chunk granularity: for every KV
+ * head, entry n_sel - 1 - i of the chunk list becomes first_new_chunk + i, for i < n_new_chunks
+ * (the list is ordered by decreasing importance, so its tail holds the least important chunks).
+ *   chunk_idx  device int32 [n_kv_heads][n_sel], as written by ts_topk_chunks (updated in place)
+ * Errors: n_new_chunks < 0 or > n_sel - n_sink_chunks (then a rebuild is due instead).
+ */
+int ts_chunk_list_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int n_sink_chunks,
+                        int first_new_chunk, int n_new_chunks, void *stream);
+
+/*
+ * Physical partial cache: copies the listed chunks into contiguous buffers, chunk j of head h
+ * to rows j*chunk_size .. of k_out[h], v_out[h] (the paper rebuilds C_p as a buffer of its own;
+ * ts_partial_kv_attn does not need this copy, it reads the chunks in place).
+ *   k_out, v_out  bf16 [n_kv_heads][n_sel * chunk_size][128]; rows of a chunk past the end of
+ *                 the cache are zero-filled
+ * chunk_size: multiple of 16, 16..1024.
+ */
+int ts_gather_chunks(const ts_kv_view *kv, const int32_t *chunk_idx, int n_sel, int chunk_size,
+                     void *k_out, void *v_out, void *stream);
+
+/*
+ * Per-chunk key sums: ksum[h][c][x] = sum_{t in chunk c} K[h][t][x] (fp32), for chunks
+ * chunk_begin <= c < chunk_end.  Eq. 2 is linear in the key, so the chunk score is a dot product
+ * of the summed group query with this sum; a caller that refreshes the sums of the chunks it
+ * appended to (only the last ones change) can rank the whole cache without re-reading it.
+ *   ksum  fp32, element (h, c, x) at ksum[h*ksum_stride_head + c*128 + x]
+ * Errors: chunk range outside [0, ceil(N / chunk_size)], chunk_size outside 1..1024.
+ */
+int ts_chunk_key_sums(const ts_kv_view *kv, int chunk_size, int64_t chunk_begin, int64_t chunk_end,
+                      float *ksum, int64_t ksum_stride_head, void *stream);
+
+/*
+ * The scores of ts_chunk_scores, computed from the key sums instead of the keys:
+ *   scores[h][c] = scale / |chunk c| * (sum_{j in group h} q[j]) . ksum[h][c]
+ * (same value up to fp32 rounding order).  n_tokens is needed for the size of the last chunk.
+ *   scores  fp32 [n_kv_heads][ceil(n_tokens / chunk_size)]
+ */
+int ts_chunk_scores_from_sums(const float *ksum, int64_t ksum_stride_head, int n_kv_heads,
+                              int64_t n_tokens, const void *q, int n_q_heads, int chunk_size,
+                              float scale, float *scores, void *stream);
+
 /*
  * Tuning hook (not needed for correct results): overrides a launch-geometry choice until
  * reset with value 0.  Names: "verify_splits" (number of cache splits per KV head);
- * "verify_impl" (1: the register-staged variant of the verification kernel instead of the
- * direct-to-LDS one); "verify_variant" (1..4: alternative workgroup shapes);
+ * "verify_variant" (1..5: alternative kernel shapes of the verification pass);
  * "verify_stage" (1: ts_tree_verify_attn enqueues only its split kernel, 2: only its merge
  * kernel -- for timing one kernel alone; outputs are then not meaningful).  Returns TS_OK, or
  * TS_ERR_UNSUPPORTED for an unknown name or a value the kernels cannot run.  The same

@@ -4,10 +4,12 @@ Thin Python front end of ``libtokenswift_hip.so`` (C ABI in ``include/tokenswift
 importance scores, top-k chunk selection, partial-KV attention and tree-verification attention
 as hand-written gfx950 kernels.  PyTorch is used only for device memory and streams.
 """
-from .binding import (TokenSwiftError, chunk_scores, lib_path, load_library, partial_kv_attn,
-                      topk_chunks, tree_verify_attn, tune_set, version, workspace_bytes,
+from .binding import (TokenSwiftError, append_accepted, chunk_key_sums, chunk_list_admit, chunk_scores,
+                      chunk_scores_from_sums, gather_chunks, lib_path, load_library, partial_kv_attn,
+                      refresh_due, topk_chunks, tree_verify_attn, tune_set, version, workspace_bytes,
                       OP_PARTIAL_ATTN, OP_TREE_VERIFY)
 
-__all__ = ["TokenSwiftError", "chunk_scores", "lib_path", "load_library", "partial_kv_attn",
+__all__ = ["TokenSwiftError", "append_accepted", "chunk_key_sums", "chunk_list_admit", "chunk_scores_from_sums",
+           "gather_chunks", "refresh_due", "chunk_scores", "lib_path", "load_library", "partial_kv_attn",
            "topk_chunks", "tree_verify_attn", "tune_set", "version", "workspace_bytes",
            "OP_PARTIAL_ATTN", "OP_TREE_VERIFY"]

@@ -62,8 +62,16 @@ def load_library():
     lib.ts_partial_kv_attn.argtypes = [kvp, vp, ci, vp, ci, ci, cf, vp, vp, vp, ctypes.c_size_t, vp]
     lib.ts_tree_verify_attn.argtypes = [kvp, vp, ci, vp, vp, ctypes.POINTER(ctypes.c_int32), ci, cf,
                                         vp, vp, vp, ctypes.c_size_t, vp]
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.ts_append_accepted.argtypes = [kvp, vp, vp, ci, i32p, ci, vp]
+    lib.ts_refresh_due.argtypes = [i64, i64, i64, i64]
+    lib.ts_chunk_list_admit.argtypes = [vp, ci, ci, ci, ci, ci, vp]
+    lib.ts_gather_chunks.argtypes = [kvp, vp, ci, ci, vp, vp, vp]
+    lib.ts_chunk_key_sums.argtypes = [kvp, ci, i64, i64, vp, i64, vp]
+    lib.ts_chunk_scores_from_sums.argtypes = [vp, i64, ci, i64, vp, ci, ci, cf, vp, vp]
     for name in ("ts_tune_set", "ts_chunk_scores", "ts_topk_chunks", "ts_partial_kv_attn",
-                 "ts_tree_verify_attn"):
+                 "ts_tree_verify_attn", "ts_append_accepted", "ts_refresh_due", "ts_chunk_list_admit",
+                 "ts_gather_chunks", "ts_chunk_key_sums", "ts_chunk_scores_from_sums"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -190,3 +198,78 @@ def tree_verify_attn(q_tree: torch.Tensor, k: Optional[torch.Tensor], v: Optiona
                                    lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
                                    workspace.numel(), _stream()), "ts_tree_verify_attn")
     return (out, lse) if lse is not None else out
+
+
+# ---- cache maintenance -----------------------------------------------------------------------
+def append_accepted(k: torch.Tensor, v: torch.Tensor, n_tokens: int, k_tree: torch.Tensor, v_tree: torch.Tensor,
+                    accepted: Sequence[int]) -> int:
+    """k/v [Hkv,cap,128] bf16 cache buffers holding n_tokens tokens; writes the accepted tree rows
+    behind them (in place) and returns the new token count."""
+    lib = load_library()
+    if n_tokens + len(accepted) > k.shape[1]:
+        raise ValueError("cache capacity exceeded")
+    kv = _KvView(k.data_ptr(), v.data_ptr(), int(n_tokens), k.shape[0], k.shape[2], k.stride(0), k.stride(1))
+    if k.stride(2) != 1 or v.stride() != k.stride():
+        raise ValueError("K and V must share strides, innermost stride 1")
+    k_tree, v_tree = k_tree.contiguous(), v_tree.contiguous()
+    acc = (ctypes.c_int32 * len(accepted))(*[int(x) for x in accepted])
+    _check(lib.ts_append_accepted(ctypes.byref(kv), k_tree.data_ptr(), v_tree.data_ptr(), k_tree.shape[0], acc,
+                                  len(accepted), _stream()), "ts_append_accepted")
+    return n_tokens + len(accepted)
+
+
+def refresh_due(n_tokens: int, n_tokens_at_refresh: int, budget_tokens: int, sink_tokens: int) -> bool:
+    rc = load_library().ts_refresh_due(int(n_tokens), int(n_tokens_at_refresh), int(budget_tokens), int(sink_tokens))
+    if rc < 0:
+        _check(rc, "ts_refresh_due")
+    return bool(rc)
+
+
+def chunk_list_admit(chunk_idx: torch.Tensor, n_sink_chunks: int, first_new_chunk: int, n_new_chunks: int) -> torch.Tensor:
+    """chunk_idx int32 [Hkv,n_sel] (contiguous, updated in place)."""
+    if not chunk_idx.is_contiguous():
+        raise ValueError("chunk_idx must be contiguous")
+    _check(load_library().ts_chunk_list_admit(chunk_idx.data_ptr(), chunk_idx.shape[0], chunk_idx.shape[1],
+                                              int(n_sink_chunks), int(first_new_chunk), int(n_new_chunks), _stream()),
+           "ts_chunk_list_admit")
+    return chunk_idx
+
+
+def gather_chunks(k: torch.Tensor, v: torch.Tensor, chunk_idx: torch.Tensor, chunk_size: int):
+    """-> (k_out, v_out) bf16 [Hkv, n_sel*chunk_size, 128]."""
+    kv = _view(k, v)
+    chunk_idx = chunk_idx.contiguous()
+    n_sel = chunk_idx.shape[1]
+    k_out = torch.empty(k.shape[0], n_sel * chunk_size, HEAD_DIM, dtype=k.dtype, device=k.device)
+    v_out = torch.empty_like(k_out)
+    _check(load_library().ts_gather_chunks(ctypes.byref(kv), chunk_idx.data_ptr(), n_sel, int(chunk_size),
+                                           k_out.data_ptr(), v_out.data_ptr(), _stream()), "ts_gather_chunks")
+    return k_out, v_out
+
+
+def chunk_key_sums(k: torch.Tensor, chunk_size: int, out: Optional[torch.Tensor] = None,
+                   chunk_begin: int = 0, chunk_end: Optional[int] = None) -> torch.Tensor:
+    """k [Hkv,N,128] bf16 view -> ksum fp32 [Hkv, n_chunks(or more), 128]; only chunks
+    [chunk_begin, chunk_end) are (re)computed."""
+    kv = _view(k, None)
+    n_chunks = (k.shape[1] + chunk_size - 1) // chunk_size if chunk_size > 0 else 0
+    if out is None:
+        out = torch.zeros(k.shape[0], max(n_chunks, 1), HEAD_DIM, dtype=torch.float32, device=k.device)
+    if chunk_end is None:
+        chunk_end = n_chunks
+    _check(load_library().ts_chunk_key_sums(ctypes.byref(kv), int(chunk_size), int(chunk_begin), int(chunk_end),
+                                            out.data_ptr(), out.stride(0), _stream()), "ts_chunk_key_sums")
+    return out
+
+
+def chunk_scores_from_sums(ksum: torch.Tensor, n_tokens: int, q: torch.Tensor, chunk_size: int, scale: float,
+                           out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """ksum fp32 [Hkv, >=n_chunks, 128], q [Hq,128] bf16 -> scores fp32 [Hkv, ceil(n_tokens/chunk_size)]."""
+    n_chunks = (n_tokens + chunk_size - 1) // chunk_size if chunk_size > 0 else 0
+    q = q.contiguous()
+    if out is None:
+        out = torch.empty(ksum.shape[0], max(n_chunks, 1), dtype=torch.float32, device=ksum.device)
+    _check(load_library().ts_chunk_scores_from_sums(ksum.data_ptr(), ksum.stride(0), ksum.shape[0], int(n_tokens),
+                                                    q.data_ptr(), q.shape[0], int(chunk_size), float(scale),
+                                                    out.data_ptr(), _stream()), "ts_chunk_scores_from_sums")
+    return out

@@ -119,7 +119,12 @@ bool ts::verify_shape(int n_rows, int variant, VerifyShape *out)
     }
     const int tiles = (n_rows + 383) / 384;
     const int r = ((n_rows + tiles - 1) / tiles + 31) / 32 * 32;   // rows per tile, balanced
-    if (r <= 32) *out = VerifyShape{kWide_1x1, 32, 3};
+    if (r <= 32) {
+        if (variant == 3) *out = VerifyShape{kWide_1x1a, 32, 5};
+        else if (variant == 4) *out = VerifyShape{kWide_1x1b, 32, 2};
+        else if (variant == 5) *out = VerifyShape{kWide_1x1c, 32, 2};
+        else *out = VerifyShape{kWide_1x1, 32, 3};
+    }
     else if (r <= 64) *out = VerifyShape{kWide_1x2, 64, 2};
     else if (r <= 128) *out = VerifyShape{variant == 2 ? kWide_1x4p : kWide_1x4, 128, 2};
     else if (r <= 256) *out = VerifyShape{variant == 2 ? kWide_1x8 : kWide_2x4, 256, 1};
@@ -155,7 +160,7 @@ int ts_tune_set(const char *name, int value)
         return TS_OK;
     }
     if (strcmp(name, "verify_variant") == 0) {
-        if (value > 2) return TS_ERR_UNSUPPORTED;
+        if (value > 5) return TS_ERR_UNSUPPORTED;
         g_tune.verify_variant = value;
         return TS_OK;
     }
@@ -353,6 +358,136 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
     c.n_rows = pl.n_rows;
     c.row_pitch = pl.n_rows_pad;
     return ts::launch_combine(c, st) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int ts_append_accepted(const ts_kv_view *kv, const void *k_tree, const void *v_tree, int n_tree,
+                       const int32_t *accepted, int n_accepted, void *stream)
+{
+    if (!kv) return TS_ERR_NULL;
+    if (kv->head_dim != TS_HEAD_DIM) return TS_ERR_UNSUPPORTED;
+    if (kv->n_kv_heads < 1 || kv->n_tokens < 0) return TS_ERR_SHAPE;
+    if (!kv->k || !kv->v || !k_tree || !v_tree || !accepted) return TS_ERR_NULL;
+    if (kv->stride_token < TS_HEAD_DIM || kv->stride_head < 0) return TS_ERR_SHAPE;
+    if ((kv->stride_token % 8) != 0 || (kv->stride_head % 8) != 0) return TS_ERR_ALIGN;
+    if (!aligned16(kv->k) || !aligned16(kv->v) || !aligned16(k_tree) || !aligned16(v_tree)) return TS_ERR_ALIGN;
+    if (n_tree < 1 || n_accepted < 1) return TS_ERR_SHAPE;
+    if (n_tree > TS_MAX_TREE || n_accepted > TS_MAX_TREE) return TS_ERR_UNSUPPORTED;
+    ts::AppendParams p;
+    for (int i = 0; i < n_accepted; ++i) {
+        if (accepted[i] < 0 || accepted[i] >= n_tree) return TS_ERR_TREE;
+        p.accepted[i] = accepted[i];
+    }
+    for (int i = n_accepted; i < ts::kMaxTree; ++i) p.accepted[i] = 0;
+    p.k = static_cast<uint16_t *>(const_cast<void *>(kv->k));
+    p.v = static_cast<uint16_t *>(const_cast<void *>(kv->v));
+    p.k_tree = static_cast<const uint16_t *>(k_tree);
+    p.v_tree = static_cast<const uint16_t *>(v_tree);
+    p.stride_head = kv->stride_head;
+    p.stride_token = kv->stride_token;
+    p.n_tokens = kv->n_tokens;
+    p.n_kv_heads = kv->n_kv_heads;
+    p.n_accepted = n_accepted;
+    return ts::launch_append(p, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int ts_refresh_due(int64_t n_tokens, int64_t n_tokens_at_refresh, int64_t budget_tokens, int64_t sink_tokens)
+{
+    if (n_tokens < 0 || n_tokens_at_refresh < 0 || n_tokens_at_refresh > n_tokens || sink_tokens < 0 ||
+        budget_tokens < sink_tokens)
+        return TS_ERR_SHAPE;
+    return (n_tokens - n_tokens_at_refresh) > (budget_tokens - sink_tokens) ? 1 : 0;
+}
+
+int ts_chunk_list_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int n_sink_chunks,
+                        int first_new_chunk, int n_new_chunks, void *stream)
+{
+    if (!chunk_idx) return TS_ERR_NULL;
+    if (n_kv_heads < 1 || n_sel < 1 || n_sink_chunks < 0 || n_sink_chunks > n_sel || first_new_chunk < 0) return TS_ERR_SHAPE;
+    if (n_new_chunks < 0 || n_new_chunks > n_sel - n_sink_chunks) return TS_ERR_SHAPE;
+    if ((int64_t)first_new_chunk + n_new_chunks > 0x7fffffffLL) return TS_ERR_SHAPE;
+    if (n_new_chunks == 0) return TS_OK;
+    return ts::launch_admit(chunk_idx, n_kv_heads, n_sel, first_new_chunk, n_new_chunks,
+                            static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int ts_gather_chunks(const ts_kv_view *kv, const int32_t *chunk_idx, int n_sel, int chunk_size,
+                     void *k_out, void *v_out, void *stream)
+{
+    int rc = check_view(kv, true, false);
+    if (rc != TS_OK) return rc;
+    if (!chunk_idx || !k_out || !v_out) return TS_ERR_NULL;
+    if (n_sel < 1) return TS_ERR_SHAPE;
+    if (!partial_chunk_ok(chunk_size)) return TS_ERR_UNSUPPORTED;
+    if (!aligned16(k_out) || !aligned16(v_out)) return TS_ERR_ALIGN;
+    if ((int64_t)n_sel * chunk_size / 16 > 0x7fffffffLL) return TS_ERR_UNSUPPORTED;
+    ts::GatherParams p;
+    p.k = static_cast<const uint16_t *>(kv->k);
+    p.v = static_cast<const uint16_t *>(kv->v);
+    p.chunk_idx = chunk_idx;
+    p.k_out = static_cast<uint16_t *>(k_out);
+    p.v_out = static_cast<uint16_t *>(v_out);
+    p.stride_head = kv->stride_head;
+    p.stride_token = kv->stride_token;
+    p.n_tokens = kv->n_tokens;
+    p.n_kv_heads = kv->n_kv_heads;
+    p.n_sel = n_sel;
+    p.chunk_size = chunk_size;
+    return ts::launch_gather(p, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int ts_chunk_key_sums(const ts_kv_view *kv, int chunk_size, int64_t chunk_begin, int64_t chunk_end,
+                      float *ksum, int64_t ksum_stride_head, void *stream)
+{
+    int rc = check_view(kv, false, false);
+    if (rc != TS_OK) return rc;
+    if (!ksum) return TS_ERR_NULL;
+    if (chunk_size < 1 || chunk_size > 1024) return TS_ERR_UNSUPPORTED;
+    const int64_t n_chunks = (kv->n_tokens + chunk_size - 1) / chunk_size;
+    if (chunk_begin < 0 || chunk_end < chunk_begin || chunk_end > n_chunks) return TS_ERR_SHAPE;
+    if (ksum_stride_head < n_chunks * TS_HEAD_DIM && kv->n_kv_heads > 1) return TS_ERR_SHAPE;
+    if (!aligned16(ksum) || (ksum_stride_head % 4) != 0) return TS_ERR_ALIGN;
+    if (chunk_end == chunk_begin) return TS_OK;
+    if ((chunk_end - chunk_begin + 3) / 4 > 0x7fffffffLL) return TS_ERR_UNSUPPORTED;
+    ts::KsumParams p;
+    p.k = static_cast<const uint16_t *>(kv->k);
+    p.ksum = ksum;
+    p.stride_head = kv->stride_head;
+    p.stride_token = kv->stride_token;
+    p.ksum_stride_head = ksum_stride_head;
+    p.n_tokens = kv->n_tokens;
+    p.chunk_begin = chunk_begin;
+    p.chunk_end = chunk_end;
+    p.n_kv_heads = kv->n_kv_heads;
+    p.chunk_size = chunk_size;
+    return ts::launch_ksum(p, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int ts_chunk_scores_from_sums(const float *ksum, int64_t ksum_stride_head, int n_kv_heads,
+                              int64_t n_tokens, const void *q, int n_q_heads, int chunk_size,
+                              float scale, float *scores, void *stream)
+{
+    if (!ksum || !q || !scores) return TS_ERR_NULL;
+    int group = 0;
+    int rc = check_heads(n_q_heads, n_kv_heads, &group);
+    if (rc != TS_OK) return rc;
+    if (n_tokens < 1) return TS_ERR_SHAPE;
+    if (chunk_size < 1 || chunk_size > 1024) return TS_ERR_UNSUPPORTED;
+    const int64_t n_chunks = (n_tokens + chunk_size - 1) / chunk_size;
+    if (ksum_stride_head < n_chunks * TS_HEAD_DIM && n_kv_heads > 1) return TS_ERR_SHAPE;
+    if (!aligned16(ksum) || (ksum_stride_head % 4) != 0 || !aligned16(q)) return TS_ERR_ALIGN;
+    if ((n_chunks + 3) / 4 > 0x7fffffffLL) return TS_ERR_UNSUPPORTED;
+    ts::SumScoresParams p;
+    p.ksum = ksum;
+    p.q = static_cast<const uint16_t *>(q);
+    p.scores = scores;
+    p.ksum_stride_head = ksum_stride_head;
+    p.n_tokens = n_tokens;
+    p.n_chunks = n_chunks;
+    p.n_kv_heads = n_kv_heads;
+    p.group = group;
+    p.chunk_size = chunk_size;
+    p.scale = scale;
+    return ts::launch_sum_scores(p, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
 }  // extern "C"

@@ -78,6 +78,24 @@ __device__ __forceinline__ float xrow_sum(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
+// ---- coalesced write-back of an accumulator block through LDS --------------------------------
+// A block of ROWS x 128 fp32 sits in LDS at `region`: row r at byte r*512, its 16-byte piece q at
+// position q ^ (r & 31) (the owners of the accumulators write it that way, which keeps both their
+// writes and these reads free of bank conflicts).  Rows [0, live_rows) go to dst (row pitch 128
+// floats): 32 lanes cover one 512-byte row, so every store instruction writes two whole rows
+// instead of 64 scattered 16-byte pieces.
+template <int ROWS>
+__device__ __forceinline__ void store_rows_from_lds(const unsigned char *region, int live_rows, float *dst, int lane)
+{
+    const int pc = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int r0 = 0; r0 < ROWS; r0 += 2) {
+        const int r = r0 + half;
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(region + r * 512 + ((pc ^ (r & 31)) << 4));
+        if (r < live_rows) __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(dst + (int64_t)r * 128 + pc * 4));
+    }
+}
+
 // full-wavefront sum, result in every lane
 __device__ __forceinline__ float wave_sum(float x) { return xrow_sum(row16_sum(x)); }
 __device__ __forceinline__ float wave_max(float x) { return xrow_max(row16_max(x)); }

@@ -33,6 +33,7 @@ enum VerifyKernelId {
     kNarrow_16 = 0,   // 16x16x32 MFMA kernel, 1 wavefront x 16 rows
     kNarrow_32,       // 16x16x32 MFMA kernel, 2 wavefronts x 16 rows
     kWide_1x1,        // 32x32x16 MFMA kernel, NRB x WR: 32-row blocks per wavefront x wavefronts
+    kWide_1x1a, kWide_1x1b, kWide_1x1c,
     kWide_1x2,
     kWide_1x4,
     kWide_1x4p,       // software-pipelined main loop
@@ -100,5 +101,46 @@ struct TopkParams {
     int n_kv_heads, n_chunks, n_sink, k;
 };
 hipError_t launch_topk(const TopkParams &p, hipStream_t stream);
+
+// ---- cache maintenance (cache_kernels.hip) ------------------------------------------------------
+struct AppendParams {
+    uint16_t *k, *v;          // cache buffers (written)
+    const uint16_t *k_tree, *v_tree;   // bf16 [n_tree][n_kv_heads][128]
+    int64_t stride_head, stride_token;
+    int64_t n_tokens;         // tokens cached before the append
+    int n_kv_heads, n_accepted;
+    int32_t accepted[kMaxTree];
+};
+hipError_t launch_append(const AppendParams &p, hipStream_t stream);
+hipError_t launch_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int first_new_chunk, int n_new, hipStream_t stream);
+
+struct GatherParams {
+    const uint16_t *k, *v;
+    const int32_t *chunk_idx; // [n_kv_heads][n_sel]
+    uint16_t *k_out, *v_out;  // [n_kv_heads][n_sel * chunk_size][128]
+    int64_t stride_head, stride_token;
+    int64_t n_tokens;
+    int n_kv_heads, n_sel, chunk_size;
+};
+hipError_t launch_gather(const GatherParams &p, hipStream_t stream);
+
+struct KsumParams {
+    const uint16_t *k;
+    float *ksum;              // element (h, c, x) at h*ksum_stride_head + c*128 + x
+    int64_t stride_head, stride_token, ksum_stride_head;
+    int64_t n_tokens, chunk_begin, chunk_end;
+    int n_kv_heads, chunk_size;
+};
+hipError_t launch_ksum(const KsumParams &p, hipStream_t stream);
+
+struct SumScoresParams {
+    const float *ksum;
+    const uint16_t *q;        // bf16 [n_q_heads][128]
+    float *scores;            // [n_kv_heads][n_chunks]
+    int64_t ksum_stride_head, n_tokens, n_chunks;
+    int n_kv_heads, group, chunk_size;
+    float scale;
+};
+hipError_t launch_sum_scores(const SumScoresParams &p, hipStream_t stream);
 
 }  // namespace ts

@@ -330,27 +330,32 @@ verify_dma_kernel(const VerifyParams p)
     wait_vmcnt<0>();   // drain the loads issued past the range before the workgroup's LDS is released
 
     // ---- write the partial: (m, l) and unnormalised O for every live row ----------------------
+    // O goes through LDS (the ring is free now) so that the stores cover whole 512-byte rows.
+    if (WR > 1) asm volatile("s_barrier" ::: "memory");   // every wavefront is done with the ring, no load still targets it
+    unsigned char *region = lds + wave * (NRB * 16 * 512);
+    static_assert(WR * NRB * 16 * 512 <= NS * kStageBytes, "write-back staging must fit in the ring");
     const int n_part = p.n_split + 1;
     const int64_t part = ((int64_t)h * n_part + split) * p.n_rows_pad;
 #pragma unroll
     for (int rb = 0; rb < NRB; ++rb) {
         const int row = row0 + rb * 16 + j;
         const float l_tot = xrow_sum(l_run[rb]);
-        if (row < p.n_rows) {
-            if (quad == 0) {
-                f32x2 ml = {m_run[rb], l_tot};
-                *reinterpret_cast<f32x2 *>(p.ws_ml + (part + row) * 2) = ml;
-            }
-            float *orow = p.ws_o + (part + row) * kHeadDim;
-            // this lane holds columns dg*64 + quad*16 + 4v + i
-#pragma unroll
-            for (int dg = 0; dg < 2; ++dg)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    f32x4 o = {oacc[rb][dg][0][v], oacc[rb][dg][1][v], oacc[rb][dg][2][v], oacc[rb][dg][3][v]};
-                    *reinterpret_cast<f32x4 *>(orow + dg * 64 + quad * 16 + 4 * v) = o;
-                }
+        if (row < p.n_rows && quad == 0) {
+            f32x2 ml = {m_run[rb], l_tot};
+            *reinterpret_cast<f32x2 *>(p.ws_ml + (part + row) * 2) = ml;
         }
+        // this lane holds columns dg*64 + quad*16 + 4v + i of row j: 16-byte piece dg*16 + quad*4 + v
+        unsigned char *blk = region + rb * (16 * 512);
+#pragma unroll
+        for (int dg = 0; dg < 2; ++dg)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                f32x4 o = {oacc[rb][dg][0][v], oacc[rb][dg][1][v], oacc[rb][dg][2][v], oacc[rb][dg][3][v]};
+                *reinterpret_cast<f32x4 *>(blk + j * 512 + (((dg * 16 + quad * 4 + v) ^ j) << 4)) = o;
+            }
+        const int row_base = row0 + rb * 16;
+        if (row_base < p.n_rows)
+            store_rows_from_lds<16>(blk, p.n_rows - row_base, p.ws_o + (part + row_base) * kHeadDim, lane);
     }
 }
 

@@ -411,25 +411,35 @@ verify_wide_kernel(const VerifyParams p)
     wait_vmcnt<0>();   // drain the loads issued past the range before the workgroup's LDS is released
 
     // ---- write the partial: (m, l) and unnormalised O for every live row ----------------------
+    // O goes through LDS (the ring is free now) so that the stores cover whole 512-byte rows; a
+    // wavefront stages one 32-row block (16 KiB) at a time.  When the ring is smaller than one
+    // block per wavefront, the wavefronts take turns in groups of NS.
     const int n_part = p.n_split + 1;
     const int64_t part = ((int64_t)h * n_part + split) * p.n_rows_pad;
+    constexpr int kGroups = (WR + NS - 1) / NS;
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        if (rb < nrb_live) {
-            const int row = tile_row0 + (rb * WR + wave) * 32 + n32;
-            const float l_tot = swap32_sum(l_run[rb]);
-            if (row < p.n_rows) {
-                if (hh == 0) {
+    for (int grp = 0; grp < kGroups; ++grp) {
+        if (WR > 1) asm volatile("s_barrier" ::: "memory");   // the ring (or the previous group's staging) is free
+        if (kGroups > 1 && wave / NS != grp) continue;
+        unsigned char *region = lds + (kGroups > 1 ? wave % NS : wave) * (32 * 512);
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            if (rb < nrb_live) {
+                const int row_base = tile_row0 + (rb * WR + wave) * 32;
+                const float l_tot = swap32_sum(l_run[rb]);
+                if (row_base + n32 < p.n_rows && hh == 0) {
                     f32x2 ml = {m_run[rb], l_tot};
-                    *reinterpret_cast<f32x2 *>(p.ws_ml + (part + row) * 2) = ml;
+                    *reinterpret_cast<f32x2 *>(p.ws_ml + (part + row_base + n32) * 2) = ml;
                 }
-                float *orow = p.ws_o + (part + row) * kHeadDim;
-                // element e of oacc[rb][cb] is output column 4*(hh*4 + 8*(e/4) + e%4) + cb
+                // element e of oacc[rb][cb] is output column 4*m + cb, m = hh*4 + 8*(e/4) + e%4:
+                // the four column blocks together make 16-byte piece m of row n32
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     f32x4 o = {oacc[rb][0][e], oacc[rb][1][e], oacc[rb][2][e], oacc[rb][3][e]};
-                    *reinterpret_cast<f32x4 *>(orow + 4 * (hh * 4 + 8 * (e >> 2) + (e & 3))) = o;
+                    const int m = hh * 4 + 8 * (e >> 2) + (e & 3);
+                    *reinterpret_cast<f32x4 *>(region + n32 * 512 + ((m ^ n32) << 4)) = o;
                 }
+                store_rows_from_lds<32>(region, p.n_rows - row_base, p.ws_o + (part + row_base) * kHeadDim, lane);
             }
         }
     }
@@ -460,6 +470,9 @@ hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t 
 {
     switch (kernel_id) {
         case kWide_1x1: return launch_one<1, 1, 3, 2, false>(p, stream);
+        case kWide_1x1a: return launch_one<1, 1, 2, 2, false>(p, stream);
+        case kWide_1x1b: return launch_one<1, 1, 4, 2, false>(p, stream);
+        case kWide_1x1c: return launch_one<1, 1, 5, 2, false>(p, stream);
         case kWide_1x2: return launch_one<1, 2, 4, 2, false>(p, stream);
         case kWide_1x4: return launch_one<1, 4, 4, 2, false>(p, stream);
         case kWide_1x4p: return launch_one<1, 4, 4, 2, false, true>(p, stream);

@@ -30,8 +30,10 @@ def test_library_exports_every_declared_function(lib):
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(ts_[a-z_]+)\s*\(", text)))
-    assert names == ["ts_chunk_scores", "ts_partial_kv_attn", "ts_strerror", "ts_topk_chunks",
-                     "ts_tree_verify_attn", "ts_tune_set", "ts_version", "ts_workspace_bytes"]
+    assert names == ["ts_append_accepted", "ts_chunk_key_sums", "ts_chunk_list_admit", "ts_chunk_scores",
+                     "ts_chunk_scores_from_sums", "ts_gather_chunks", "ts_partial_kv_attn", "ts_refresh_due",
+                     "ts_strerror", "ts_topk_chunks", "ts_tree_verify_attn", "ts_tune_set", "ts_version",
+                     "ts_workspace_bytes"]
     for n in names:
         assert hasattr(lib, n), n
     assert lib.ts_version() >= 100
@@ -136,3 +138,48 @@ def test_tune_set(lib):
     assert lib.ts_tune_set(b"no_such_knob", 1) == TS_ERR_UNSUPPORTED
     assert lib.ts_tune_set(b"verify_splits", -1) == TS_ERR_UNSUPPORTED
     assert lib.ts_tune_set(None, 1) == TS_ERR_UNSUPPORTED
+
+
+def test_cache_maintenance_calls_reject_bad_arguments(lib, binding):
+    """Host-side validation only: every call below must return before anything is enqueued."""
+    kt, vt = 0x6000, 0x7000
+
+    def ap(view=None, acc=(0, 1), n_tree=4, kt_=kt, vt_=vt):
+        a = (ctypes.c_int32 * max(len(acc), 1))(*acc) if acc is not None else None
+        return lib.ts_append_accepted(ctypes.byref(view if view is not None else _view(binding)), kt_, vt_, n_tree, a,
+                                      len(acc) if acc is not None else 1, None)
+    assert ap(acc=None) == TS_ERR_NULL and ap(kt_=None) == TS_ERR_NULL
+    assert ap(view=_view(binding, v=None)) == TS_ERR_NULL
+    assert ap(acc=(0, 4)) == TS_ERR_TREE and ap(acc=(-1,)) == TS_ERR_TREE
+    assert ap(acc=()) == TS_ERR_SHAPE and ap(n_tree=0) == TS_ERR_SHAPE
+    assert ap(acc=tuple([0] * 129), n_tree=4) == TS_ERR_UNSUPPORTED
+    assert ap(view=_view(binding, d=64)) == TS_ERR_UNSUPPORTED
+    assert ap(view=_view(binding, st=132)) == TS_ERR_ALIGN
+
+    rd = lib.ts_refresh_due
+    assert rd(100, 50, 64, 16) == 1 and rd(98, 50, 64, 16) == 0 and rd(99, 50, 64, 16) == 1 and rd(50, 50, 64, 16) == 0
+    assert rd(-1, 0, 64, 16) == TS_ERR_SHAPE and rd(10, 11, 64, 16) == TS_ERR_SHAPE and rd(10, 5, 8, 16) == TS_ERR_SHAPE
+
+    ad = lambda idx=0x5000, hkv=2, n_sel=9, sink=1, first=40, n_new=2: lib.ts_chunk_list_admit(idx, hkv, n_sel, sink, first, n_new, None)
+    assert ad(idx=None) == TS_ERR_NULL
+    assert ad(n_new=9) == TS_ERR_SHAPE and ad(n_new=-1) == TS_ERR_SHAPE and ad(first=-3) == TS_ERR_SHAPE
+    assert ad(sink=10) == TS_ERR_SHAPE and ad(n_new=0) == 0          # nothing to do: no launch
+
+    ga = lambda view=None, idx=0x5000, n_sel=3, chunk=64, ko=0x8000, vo=0x9000: lib.ts_gather_chunks(
+        ctypes.byref(view if view is not None else _view(binding)), idx, n_sel, chunk, ko, vo, None)
+    assert ga(idx=None) == TS_ERR_NULL and ga(ko=None) == TS_ERR_NULL and ga(vo=None) == TS_ERR_NULL
+    assert ga(n_sel=0) == TS_ERR_SHAPE and ga(chunk=24) == TS_ERR_UNSUPPORTED and ga(ko=0x8004) == TS_ERR_ALIGN
+    assert ga(view=_view(binding, v=None)) == TS_ERR_NULL
+
+    ks = lambda view=None, chunk=64, cb=0, ce=2, out=0xa000, sh=2 * 128: lib.ts_chunk_key_sums(
+        ctypes.byref(view if view is not None else _view(binding)), chunk, cb, ce, out, sh, None)
+    assert ks(out=None) == TS_ERR_NULL
+    assert ks(ce=3) == TS_ERR_SHAPE and ks(cb=-1) == TS_ERR_SHAPE and ks(cb=2, ce=1) == TS_ERR_SHAPE   # 100 tokens: 2 chunks
+    assert ks(chunk=0) == TS_ERR_UNSUPPORTED and ks(sh=128) == TS_ERR_SHAPE and ks(sh=2 * 128 + 2) == TS_ERR_ALIGN
+    assert ks(cb=1, ce=1) == 0                                         # empty range: no launch
+
+    sf = lambda ksum=0xa000, sh=2 * 128, hkv=2, n=100, q=0x3000, hq=4, chunk=64, out=0xb000: lib.ts_chunk_scores_from_sums(
+        ksum, sh, hkv, n, q, hq, chunk, 1.0, out, None)
+    assert sf(ksum=None) == TS_ERR_NULL and sf(q=None) == TS_ERR_NULL and sf(out=None) == TS_ERR_NULL
+    assert sf(hq=3) == TS_ERR_SHAPE and sf(hq=18) == TS_ERR_UNSUPPORTED and sf(n=0) == TS_ERR_SHAPE
+    assert sf(chunk=2000) == TS_ERR_UNSUPPORTED and sf(sh=128) == TS_ERR_SHAPE
