@@ -97,33 +97,53 @@ __global__ void __launch_bounds__(256) ksum_kernel(const KsumParams p)
 }
 
 // ---- chunk scores from the key sums ------------------------------------------------------------------
-// One wavefront per chunk, two dimensions per lane.
+// A 16-lane group owns one chunk at a time (8 dimensions per lane, two 128-bit loads); a
+// wavefront covers 16 chunks, all of its loads issued before the first use.
 template <int G>
 __global__ void __launch_bounds__(256) scores_from_sums_kernel(const SumScoresParams p)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;
+    const int c = lane & 15, r = lane >> 4;
     const int h = blockIdx.y;
-    if (chunk >= p.n_chunks) return;
-    float q0 = 0.f, q1 = 0.f;
+    const int64_t chunk0 = ((int64_t)blockIdx.x * 4 + wave) * 16;
+    if (chunk0 >= p.n_chunks) return;
+    float qbar[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int jj = 0; jj < G; ++jj) {
-        const uint32_t raw = *reinterpret_cast<const uint32_t *>(p.q + ((int64_t)h * G + jj) * kHeadDim + lane * 2);
-        q0 += bf16lo_to_f32(raw);
-        q1 += bf16hi_to_f32(raw);
+        const u32x4 raw = *reinterpret_cast<const u32x4 *>(p.q + ((int64_t)h * G + jj) * kHeadDim + c * 8);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            qbar[2 * w] += bf16lo_to_f32(raw[w]);
+            qbar[2 * w + 1] += bf16hi_to_f32(raw[w]);
+        }
     }
-    const f32x2 s = *reinterpret_cast<const f32x2 *>(p.ksum + (int64_t)h * p.ksum_stride_head + chunk * kHeadDim + lane * 2);
-    const float d = wave_sum(fmaf(q0, s[0], q1 * s[1]));
-    int64_t count = p.n_tokens - chunk * p.chunk_size;
-    if (count > p.chunk_size) count = p.chunk_size;
-    if (lane == 0) p.scores[(int64_t)h * p.n_chunks + chunk] = p.scale * d / (float)count;
+    const float *base = p.ksum + (int64_t)h * p.ksum_stride_head + c * 8;
+    f32x4 a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t chunk = chunk0 + i * 4 + r;
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        a[i] = chunk < p.n_chunks ? *reinterpret_cast<const f32x4 *>(base + chunk * kHeadDim) : z;
+        b[i] = chunk < p.n_chunks ? *reinterpret_cast<const f32x4 *>(base + chunk * kHeadDim + 4) : z;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t chunk = chunk0 + i * 4 + r;
+        float d = 0.f;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) d = fmaf(qbar[x], a[i][x], fmaf(qbar[4 + x], b[i][x], d));
+        d = row16_sum(d);
+        int64_t count = p.n_tokens - chunk * p.chunk_size;
+        if (count > p.chunk_size) count = p.chunk_size;
+        if (c == 0 && chunk < p.n_chunks) p.scores[(int64_t)h * p.n_chunks + chunk] = p.scale * d / (float)count;
+    }
 }
 
 template <int G>
 hipError_t launch_sum_scores_g(const SumScoresParams &p, hipStream_t stream)
 {
-    dim3 grid((unsigned)((p.n_chunks + 3) / 4), p.n_kv_heads);
+    dim3 grid((unsigned)((p.n_chunks + 63) / 64), p.n_kv_heads);
     hipLaunchKernelGGL(scores_from_sums_kernel<G>, grid, dim3(256), 0, stream, p);
     return hipGetLastError();
 }

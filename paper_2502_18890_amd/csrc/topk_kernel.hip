@@ -8,7 +8,8 @@
 //   1. radix select, 8 bits per pass from the top: a 256-bin LDS histogram of the candidates
 //      that still match the decided prefix, one wavefront scans it from the top bin down and
 //      fixes the next digit of the k-th largest key.  Digits that are the same for all keys
-//      (the upper bytes of ~index) are skipped: 4 passes for the score + 1..3 for the index.
+//      (the upper bytes of ~index) are skipped: 4 passes for the score + 1..3 for the index,
+//      and the index passes are skipped too unless equal scores straddle the cut.
 //   2. the k keys >= the k-th largest are compacted into LDS (slot order is arbitrary);
 //   3. they are put in order: by rank counting (k <= 256: each key counts the larger ones,
 //      all reads are LDS broadcasts) or by a bitonic network in LDS (larger k).
@@ -40,7 +41,7 @@ __global__ void __launch_bounds__(1024) topk_kernel(const TopkParams p, int n_so
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     uint32_t *hist = reinterpret_cast<uint32_t *>(lds_raw);
-    uint32_t *ctl = reinterpret_cast<uint32_t *>(lds_raw + kHistBytes);   // [0] digit, [1] remaining k, [2] slot counter
+    uint32_t *ctl = reinterpret_cast<uint32_t *>(lds_raw + kHistBytes);   // [0] digit, [1] remaining k, [2] slot counter, [3] size of the chosen bin
     uint64_t *sel = reinterpret_cast<uint64_t *>(lds_raw + kHistBytes + kCtlBytes);
     const int sel_cap = p.k > kRankCountMax ? n_sort : p.k;
     uint32_t *skeys = reinterpret_cast<uint32_t *>(sel + sel_cap);
@@ -96,6 +97,7 @@ __global__ void __launch_bounds__(1024) topk_kernel(const TopkParams p, int n_so
                 if (above < kk && kk <= above + c[j]) {
                     ctl[0] = (uint32_t)(255 - (4 * tid + j));
                     ctl[1] = kk - above;
+                    ctl[3] = c[j];
                 }
                 above += c[j];
             }
@@ -104,6 +106,9 @@ __global__ void __launch_bounds__(1024) topk_kernel(const TopkParams p, int n_so
         prefix |= (uint64_t)ctl[0] << shift;
         mask |= 0xffull << shift;
         kk = ctl[1];
+        // The score is decided and every key that shares the k-th largest score is wanted: no tie
+        // straddles the cut, so the index digits need not be examined.
+        if (pass == 3 && ctl[3] == kk) break;
     }
 
     // ---- 2. compact the k keys >= the k-th largest -------------------------------------------
