@@ -32,15 +32,20 @@ struct VerifyParams {
 enum VerifyKernelId {
     kNarrow_16 = 0,   // 16x16x32 MFMA kernel, 1 wavefront x 16 rows
     kNarrow_32,       // 16x16x32 MFMA kernel, 2 wavefronts x 16 rows
-    kWide_1x1,        // 32x32x16 MFMA kernel, NRB x WR: 32-row blocks per wavefront x wavefronts
-    kWide_1x1a, kWide_1x1b, kWide_1x1c,
+    // 32x32x16 MFMA kernel, <32-row blocks per wavefront> x <wavefronts along the rows>
+    kWide_1x1,
+    kWide_1x1b,       // deeper ring, two workgroups per CU
     kWide_1x2,
     kWide_1x4,
     kWide_1x4p,       // software-pipelined main loop
+    kWide_1x4k2,      // two key groups, query fragments in LDS
+    kWide_1x4k3,      // three key groups, query fragments in LDS
     kWide_2x4,
     kWide_1x8,
     kWide_3x4,
     kWide_3x4q,       // query fragments in LDS
+    kWide_1x10,       // query fragments in LDS
+    kWide_1x12,       // query fragments in LDS
 };
 struct VerifyShape {
     int kernel_id;

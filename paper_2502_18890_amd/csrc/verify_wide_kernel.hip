@@ -6,8 +6,13 @@
 // and once g*T reaches ~100 rows the pass is no longer purely HBM-bound: the matrix and vector
 // units have to be kept busy at the same time.  Work decomposition: one workgroup = one KV
 // head x one contiguous range of cached tokens (split index n_split = the tree tokens with the
-// ancestor mask) x up to 32*NRB*WR query rows; 32-row blocks are dealt round-robin to the WR
-// wavefronts, every wavefront applies each 32-key tile to its own blocks.
+// ancestor mask) x up to 32*NRB*WR query rows; 32-row blocks are dealt round-robin to WR
+// wavefronts, every wavefront applies a 32-key tile to its own blocks.  A workgroup may hold KG
+// such sets of WR wavefronts ("key groups"): group g takes tiles g, g+KG, ... of the range with
+// its own accumulators and the groups are merged through LDS at the end.  That puts KG
+// wavefronts on every SIMD (more latency hiding, matrix and vector work of different tiles
+// overlap) while the workgroup still writes a single partial and shares one copy of the query
+// fragments.
 //
 //   S^T = K . Q^T    A = K tile  (32 keys x 16 dims),   B = Q^T (16 dims x 32 rows), 8 steps
 //   O^T += V^T . P^T A = V^T     (32 cols x 16 keys),   B = P^T (16 keys x 32 rows), 2 steps x 4 column blocks
@@ -16,17 +21,19 @@
 // mod 32): running max and sum are per-lane state, the row max needs one v_permlane32_swap, and
 // the probabilities a lane computes are exactly the B-operand elements it must supply for the
 // second product (the contraction order of keys is permuted the same way on the V^T side).
-// The V^T operand needs 8 keys of one column per lane: a lane reads 4 consecutive columns of
-// each of its 16 keys (ds_read_b64) and regroups them with v_perm_b32 into the operands of 4
-// column blocks; column block c then holds columns 4m+c, so a lane ends up with runs of 4
-// consecutive output columns and writes its partial with 128-bit stores.
+// The V^T operand needs 8 keys of one column per lane while V sits key-major in LDS: that is what
+// ds_read_b64_tr_b16 is for.  Within 16 lanes, source lane i points at 4 consecutive columns of
+// one key and result lane j receives column j%4 of the sources 4r + j/4 (r = 0..3); with source
+// i -> (key base + i/4, columns 4*(i%4)..) a result lane gets 4 consecutive keys of column j, and
+// two such reads make one operand with no register shuffling.
 // P is split into hi + lo (both bf16) and multiplied twice, which keeps ~16 bits per weight.
 //
 // Data path: buffer_load_dwordx4 ... lds moves four 256-byte rows per instruction from HBM
 // straight into an NS-stage LDS ring (no VGPR staging); 16-byte pieces are permuted on the way
 // in so that operand reads are bank-conflict free:
 //   K rows: LDS piece pos of row R holds global piece pos ^ (R mod 16);
-//   V rows: LDS piece pos of row R holds global piece pos ^ 8*((R/4) mod 2).
+//   V rows: LDS piece pos of row R holds global piece pos ^ 4*(R mod 4)  (the four keys a
+//           transposed read touches land in four different 64-byte bank groups).
 // Rows past the end of a range are cut off by the buffer descriptor's byte count; the ring is
 // cleared once so a stage never holds anything but finite values (a masked key adds 0 * V).
 #include <type_traits>
@@ -40,6 +47,9 @@ namespace {
 
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 constexpr int kTileKeys = 32;
 constexpr int kStageBytes = kTileKeys * 512;   // K half then V half
@@ -65,23 +75,30 @@ __device__ __forceinline__ float swap32_sum(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-// NRB: 32-row blocks per wavefront; WR: wavefronts per workgroup; NS: LDS stages (NS-2 tiles in
-// flight while two are resident); OCC: wavefronts per SIMD the register budget is cut for;
-// QLDS: query fragments live in LDS instead of registers.
-template <int NRB, int WR, int NS, int OCC, bool QLDS, bool PIPE>
-__global__ void __launch_bounds__(64 * WR) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
+// smallest divisor of 16 that is >= ceil(16 / wr): the first 16/LPW wavefronts of a key group issue
+// LPW tile-load instructions each, the others none (so every wavefront's vmcnt arithmetic holds)
+constexpr int loads_per_wave(int wr) { return wr >= 16 ? 1 : (wr >= 8 ? 2 : (wr >= 4 ? 4 : (wr >= 2 ? 8 : 16))); }
+
+// NRB: 32-row blocks per wavefront; WR: wavefronts per key group (along the query rows); KG: key
+// groups; NS: LDS stages per key group (one or two tiles resident, the others in flight); OCC:
+// wavefronts per SIMD the register budget is cut for; QLDS: query fragments live in LDS instead
+// of registers; PIPE: S^T of the next tile is issued before the softmax of the current one.
+template <int NRB, int WR, int KG, int NS, int OCC, bool QLDS, bool PIPE>
+__global__ void __launch_bounds__(64 * WR * KG) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 verify_wide_kernel(const VerifyParams p)
 {
-    constexpr int NT = 64 * WR;
-    constexpr int LPW = 16 / WR;   // load instructions per wavefront per tile (16 x 1 KiB = one tile)
+    constexpr int NT = 64 * WR * KG;
+    constexpr int LPW = loads_per_wave(WR);   // load instructions per loading wavefront per tile (16 x 1 KiB = one tile)
     constexpr int RES = PIPE ? 2 : 1;   // tiles resident in LDS while the others are in flight
-    static_assert(16 % WR == 0 && NS >= RES + 1, "bad shape");
+    static_assert(NS >= RES + 1, "bad shape");
     static_assert((NS - RES - 1) * LPW <= 63, "too many loads in flight for vmcnt");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = wave_id % WR;   // position along the query rows
+    const int kg = wave_id / WR;     // key group
     const int n32 = lane & 31;     // query row within a 32-row block / key row of a K operand
     const int hh = lane >> 5;      // which half of the contraction slice this lane supplies
     const int j = lane & 15;       // 16-byte piece a lane moves in a tile load
@@ -109,7 +126,7 @@ verify_wide_kernel(const VerifyParams p)
     // ---- clear the ring --------------------------------------------------------------------
     {
         const u32x4 z = {0u, 0u, 0u, 0u};
-        for (int off = tid * 16; off < NS * kStageBytes; off += NT * 16) *reinterpret_cast<u32x4 *>(lds + off) = z;
+        for (int off = tid * 16; off < KG * NS * kStageBytes; off += NT * 16) *reinterpret_cast<u32x4 *>(lds + off) = z;
     }
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS traffic only
 
@@ -121,7 +138,7 @@ verify_wide_kernel(const VerifyParams p)
     const int nrb_live = __builtin_amdgcn_readfirstlane(n_blocks > wave ? (n_blocks - wave + WR - 1) / WR : 0);
 
     // ---- query fragments (MFMA B operand): loads issued now, awaited after the prefetch is out --
-    unsigned char *qlds = lds + NS * kStageBytes + (wave * NRB * 32) * kQRowBytes;
+    unsigned char *qlds = lds + KG * NS * kStageBytes + (wave * NRB * 32) * kQRowBytes;   // shared by the key groups
     u32x4 qraw[NRB][8];
     uint64_t amask_lo[NRB], amask_hi[NRB];   // ancestor-or-self bits of tree nodes 0..63 and 64..127
 #pragma unroll
@@ -136,7 +153,7 @@ verify_wide_kernel(const VerifyParams p)
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             u32x4 raw = {0u, 0u, 0u, 0u};
-            if (live) raw = *reinterpret_cast<const u32x4 *>(qrow + ks * 16 + hh * 8);
+            if (live && (!QLDS || kg == 0)) raw = *reinterpret_cast<const u32x4 *>(qrow + ks * 16 + hh * 8);
             qraw[rb][ks] = raw;
         }
     }
@@ -155,17 +172,22 @@ verify_wide_kernel(const VerifyParams p)
 
     // ---- HBM -> LDS -------------------------------------------------------------------------
     // Load instruction ii (0..15) of a tile fills LDS block ii: K rows 4ii..4ii+3 for ii < 8,
-    // V rows 4(ii-8).. for ii >= 8.  This wavefront issues ii = wave*LPW .. wave*LPW+LPW-1.
+    // V rows 4(ii-8).. for ii >= 8.  Wavefront `wave` of a key group issues ii = wave*LPW ..
+    // wave*LPW+LPW-1 of that group's tiles if those are < 16, else nothing.  Group tile number u of
+    // key group kg is tile u*KG + kg of the range and lives in stage (u % NS)*KG + kg.
+    const bool loader = wave * LPW < 16;
     uint32_t goff[LPW];
 #pragma unroll
     for (int i = 0; i < LPW; ++i) {
         const int ii = wave * LPW + i;
         const int R = 4 * (ii & 7) + quad;                       // row of the tile this lane fetches from
-        const int f = (ii >= 8) ? (((R >> 2) & 1) << 3) : (R & 15);
+        const int f = (ii >= 8) ? ((R & 3) << 2) : (R & 15);
         goff[i] = (uint32_t)(R * tstride * 2 + ((j ^ f) << 4));
     }
-    auto issue_tile = [&](int64_t tile) {
-        const int64_t t0 = t_begin + tile * kTileKeys;
+    auto stage_of = [&](int64_t u) { return lds + ((int)(u % NS) * KG + kg) * kStageBytes; };
+    auto issue_tile = [&](int64_t u) {
+        if (!loader) return;
+        const int64_t t0 = t_begin + (u * KG + kg) * kTileKeys;
         const int64_t span = t0 < t_end ? (t_end - t0 - 1) * tstride * 2 + 256 : 0;   // bytes up to the end of the last valid row
         const uint32_t nrec = span > 0xffffffffLL ? 0xffffffffu : (uint32_t)span;
         const int64_t tb = t0 < t_end ? t0 : t_begin;            // keep the base inside the allocation
@@ -173,7 +195,7 @@ verify_wide_kernel(const VerifyParams p)
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(kbase + tb * tstride), 0, nrec, 0x00020000);
         const __amdgpu_buffer_rsrc_t rv =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(vbase + tb * tstride), 0, nrec, 0x00020000);
-        unsigned char *stage = lds + (int)(tile % NS) * kStageBytes;
+        unsigned char *stage = stage_of(u);
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int ii = wave * LPW + i;                       // wave-uniform
@@ -189,10 +211,18 @@ verify_wide_kernel(const VerifyParams p)
     int koff[8];   // K operand of step ks: key row n32, global piece 2ks+hh
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) koff[ks] = n32 * 256 + ((((ks << 1) | hh) ^ (n32 & 15)) << 4);
-    // V: this lane's keys are hh*4 + 8i + v (i, v = 0..3); it reads columns 4*n32 .. 4*n32+3 of each
-    const int voff = kVHalf + hh * 1024 + ((((n32 >> 1)) ^ (hh << 3)) << 4) + ((n32 & 1) << 3);
+    // V (transposed reads): as a source, this lane points at key 4*hh + (lane%16)/4 of each group of
+    // 8 keys and at columns 32*cb + 16*((lane/16)%2) + 4*(lane%4) .. +3
+    int voff[4];
+    {
+        const int jb = lane & 15, i4 = jb >> 2, ilo = jb & 3, mh = (lane >> 4) & 1;
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+            voff[cb] = kVHalf + (4 * hh + i4) * 256 + ((4 * (cb ^ i4) + 2 * mh + (ilo >> 1)) << 4) + ((ilo & 1) << 3);
+    }
 
     const int64_t n_tiles = (t_end - t_begin + kTileKeys - 1) / kTileKeys;
+    const int64_t n_steps = (n_tiles + KG - 1) / KG;   // group tiles per key group (some groups may run one empty)
 #pragma unroll
     for (int s = 0; s < NS - RES; ++s) issue_tile(s);   // tiles past the range load nothing but still count
 
@@ -206,12 +236,14 @@ verify_wide_kernel(const VerifyParams p)
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             asm volatile("" ::"v"(qraw[rb][ks]));
-            if (QLDS)   // each wavefront later reads back only what it wrote itself
-                *reinterpret_cast<u32x4 *>(qlds + (rb * 32 + n32) * kQRowBytes + (ks * 16 + hh * 8) * 2) = qraw[rb][ks];
-            else
+            if (QLDS) {   // written once, by key group 0; first read after the first barrier of the main loop
+                if (kg == 0)
+                    *reinterpret_cast<u32x4 *>(qlds + (rb * 32 + n32) * kQRowBytes + (ks * 16 + hh * 8) * 2) = qraw[rb][ks];
+            } else
                 qf[rb][ks] = __builtin_bit_cast(bf16x8, qraw[rb][ks]);
         }
     }
+    if (QLDS) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the fragments are in LDS before this wavefront reaches the first barrier
 
     // One 32-key tile against all of this wavefront's row blocks.  RAGGED tiles (the last one of
     // a range, every tile of the tree split) mask keys; full tiles carry no masking code.
@@ -228,15 +260,20 @@ verify_wide_kernel(const VerifyParams p)
         for (int rb = 0; rb < L; ++rb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) sacc[rb][e] = 0.f;
+        // all eight key operands are requested before the first product, so that the chain of
+        // matrix instructions waits for LDS once, not eight times
+        bf16x8 ka[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) ka[ks] = *reinterpret_cast<const bf16x8 *>(stage + koff[ks]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(stage + koff[ks]);
 #pragma unroll
             for (int rb = 0; rb < L; ++rb) {
                 const bf16x8 b = QLDS ? *reinterpret_cast<const bf16x8 *>(
                                             qlds + (rb * 32 + n32) * kQRowBytes + (ks * 16 + hh * 8) * 2)
                                       : qf[QLDS ? 0 : rb][ks];
-                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, sacc[rb], 0, 0, 0);
+                sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], b, sacc[rb], 0, 0, 0);
             }
         }
     };
@@ -248,26 +285,17 @@ verify_wide_kernel(const VerifyParams p)
         constexpr int L = decltype(live_tag)::value;
         constexpr bool RAGGED = decltype(ragged_tag)::value;
 
-        // V^T operands: vt[cb][s] = column 4*n32+cb, keys hh*4 + 8*(2s + e/4) + e%4 (e = 0..7)
+        // V^T operands: vt[cb][s] = column 32*cb + n32, keys 4*hh + 16*s + 8*(e/4) + e%4 (e = 0..7)
         bf16x8 vt[4][2];
-        {
-            u32x2 vr[16];
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                vr[e] = *reinterpret_cast<const u32x2 *>(stage + voff + (8 * (e >> 2) + (e & 3)) * 256);
+        for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-                for (int s = 0; s < 2; ++s) {
-                    u32x4 a;
-#pragma unroll
-                    for (int w = 0; w < 4; ++w) {
-                        const uint32_t x = vr[8 * s + 2 * w][cb >> 1], y = vr[8 * s + 2 * w + 1][cb >> 1];
-                        a[w] = (cb & 1) ? __builtin_amdgcn_perm(y, x, 0x07060302u) : __builtin_amdgcn_perm(y, x, 0x05040100u);
-                    }
-                    vt[cb][s] = __builtin_bit_cast(bf16x8, a);
-                }
-        }
+            for (int s = 0; s < 2; ++s) {
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(stage + voff[cb] + (16 * s) * 256));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(stage + voff[cb] + (16 * s + 8) * 256));
+                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                vt[cb][s] = __builtin_bit_cast(bf16x8, both);
+            }
 
         // Row maxima (raw logits; scale > 0 commutes with max).  Element e of sacc is key
         // hh*4 + 8*(e/4) + e%4 of the tile, for query row n32.  m_run is a reference point, not
@@ -280,7 +308,9 @@ verify_wide_kernel(const VerifyParams p)
         for (int rb = 0; rb < L; ++rb) {
             if (RAGGED) {
                 uint64_t tile_ok;
-                if (is_tree) {
+                if (t0 >= t_end) {   // a key group's tile past the end of the range: no keys
+                    tile_ok = 0ull;
+                } else if (is_tree) {
                     const uint64_t w = (t0 & 64) ? amask_hi[rb] : amask_lo[rb];
                     tile_ok = w >> (t0 & 63);
                 } else {
@@ -345,62 +375,63 @@ verify_wide_kernel(const VerifyParams p)
         }
     };
 
-    // Main loop.  Tile t lives in stage t % NS.  Plain form: one tile resident, NS-1 in flight.
-    // Pipelined form: step `it` needs the keys of tile it+1 and the values of tile it, so two
-    // tiles are resident and NS-2 in flight.  Every wavefront of the workgroup runs the same
-    // number of steps (one barrier each), whichever instantiation of the body it takes.
-    const int64_t n_full = is_tree ? 0 : (t_end - t_begin) / kTileKeys;
-    auto sync_and_refill = [&](int64_t landed_tile) {
-        // this wavefront's pieces of `landed_tile` have landed: the NS-RES-1 tiles issued after it
+    // Main loop over group tiles u = 0 .. n_steps-1 (tile u*KG + kg of the range).  Plain form: one
+    // group tile resident, NS-1 in flight.  Pipelined form: step u needs the keys of group tile u+1
+    // and the values of group tile u, so two are resident and NS-2 in flight.  Every wavefront of
+    // the workgroup runs the same number of steps (one barrier each), whichever instantiation of
+    // the body it takes.
+    const int64_t n_full_steps = is_tree ? 0 : ((t_end - t_begin) / kTileKeys) / KG;   // steps whose tiles are full for every key group
+    auto t0_of = [&](int64_t u) { return t_begin + (u * KG + kg) * kTileKeys; };
+    auto sync_and_refill = [&](int64_t landed) {
+        // this wavefront's pieces of group tile `landed` have landed: the NS-RES-1 issued after it
         // may still be in flight
         wait_vmcnt<(NS - RES - 1) * LPW>();
-        // ... and everyone's; all are done with tile landed_tile-RES.  A bare s_barrier: __syncthreads()
-        // would add a fence that waits for every outstanding load, i.e. for the whole prefetched ring.
-        if (WR > 1) asm volatile("s_barrier" ::: "memory");
-        issue_tile(landed_tile + NS - RES);           // refills the stage that tile landed_tile-RES occupied
+        // ... and everyone's; all are done with group tile landed-RES.  A bare s_barrier:
+        // __syncthreads() would add a fence that waits for every outstanding load, i.e. for the
+        // whole prefetched ring.
+        if (WR * KG > 1) asm volatile("s_barrier" ::: "memory");
+        issue_tile(landed + NS - RES);                // refills the stage that group tile landed-RES occupied
     };
     auto run = [&](auto live_tag) {
         constexpr int L = decltype(live_tag)::value;
         f32x16 s_cur[L > 0 ? L : 1];
         if (!PIPE) {
-            // full tiles first, then (cache ranges) at most one ragged tile; the tree split is all ragged
-            auto step = [&](auto ragged_tag, int64_t it) {
-                sync_and_refill(it);
+            // full tiles first, then the ragged end; the tree split is all ragged
+            auto step = [&](auto ragged_tag, int64_t u) {
+                sync_and_refill(u);
                 if (L > 0) {
-                    const unsigned char *stage = lds + (int)(it % NS) * kStageBytes;
-                    qk_tile(live_tag, stage, s_cur);
-                    pv_tile(live_tag, ragged_tag, stage, t_begin + it * kTileKeys, s_cur);
+                    qk_tile(live_tag, stage_of(u), s_cur);
+                    pv_tile(live_tag, ragged_tag, stage_of(u), t0_of(u), s_cur);
                 }
             };
-            for (int64_t it = 0; it < n_full; ++it) step(std::false_type{}, it);
-            for (int64_t it = n_full; it < n_tiles; ++it) step(std::true_type{}, it);
+            for (int64_t u = 0; u < n_full_steps; ++u) step(std::false_type{}, u);
+            for (int64_t u = n_full_steps; u < n_steps; ++u) step(std::true_type{}, u);
             return;
         }
-        // Pipelined: S^T of tile it+1 is issued before the softmax of tile it.  The steady state is
-        // unrolled twice so that the two logit buffers swap roles without copies.
+        // Pipelined: S^T of group tile u+1 is issued before the softmax of group tile u.  The
+        // steady state is unrolled twice so that the two logit buffers swap roles without copies.
         f32x16 s_nxt[L > 0 ? L : 1];
-        auto stage_of = [&](int64_t t) { return lds + (int)(t % NS) * kStageBytes; };
-        sync_and_refill(0);   // prologue: tile 0
+        sync_and_refill(0);   // prologue: group tile 0
         if (L > 0) qk_tile(live_tag, stage_of(0), s_cur);
-        int64_t it = 0;
-        for (; it + 2 < n_full; it += 2) {   // tiles it, it+1 full; tiles it+1, it+2 exist
-            sync_and_refill(it + 1);
+        int64_t u = 0;
+        for (; u + 2 < n_full_steps; u += 2) {   // group tiles u, u+1 full; u+1, u+2 exist
+            sync_and_refill(u + 1);
             if (L > 0) {
-                qk_tile(live_tag, stage_of(it + 1), s_nxt);
-                pv_tile(live_tag, std::false_type{}, stage_of(it), t_begin + it * kTileKeys, s_cur);
+                qk_tile(live_tag, stage_of(u + 1), s_nxt);
+                pv_tile(live_tag, std::false_type{}, stage_of(u), t0_of(u), s_cur);
             }
-            sync_and_refill(it + 2);
+            sync_and_refill(u + 2);
             if (L > 0) {
-                qk_tile(live_tag, stage_of(it + 2), s_cur);
-                pv_tile(live_tag, std::false_type{}, stage_of(it + 1), t_begin + (it + 1) * kTileKeys, s_nxt);
+                qk_tile(live_tag, stage_of(u + 2), s_cur);
+                pv_tile(live_tag, std::false_type{}, stage_of(u + 1), t0_of(u + 1), s_nxt);
             }
         }
-        for (; it < n_tiles; ++it) {         // the last few tiles, ragged ones included
-            sync_and_refill(it + 1);
+        for (; u < n_steps; ++u) {               // the last few group tiles, ragged ones included
+            sync_and_refill(u + 1);
             if (L > 0) {
-                if (it + 1 < n_tiles) qk_tile(live_tag, stage_of(it + 1), s_nxt);
-                if (it < n_full) pv_tile(live_tag, std::false_type{}, stage_of(it), t_begin + it * kTileKeys, s_cur);
-                else pv_tile(live_tag, std::true_type{}, stage_of(it), t_begin + it * kTileKeys, s_cur);
+                if (u + 1 < n_steps) qk_tile(live_tag, stage_of(u + 1), s_nxt);
+                if (u < n_full_steps) pv_tile(live_tag, std::false_type{}, stage_of(u), t0_of(u), s_cur);
+                else pv_tile(live_tag, std::true_type{}, stage_of(u), t0_of(u), s_cur);
 #pragma unroll
                 for (int rb = 0; rb < L; ++rb) s_cur[rb] = s_nxt[rb];
             }
@@ -408,20 +439,63 @@ verify_wide_kernel(const VerifyParams p)
     };
     if (nrb_live == NRB) run(std::integral_constant<int, NRB>{});
     else run(std::integral_constant<int, NRB - 1>{});   // round-robin dealing: never fewer than NRB-1 unless none at all
-    wait_vmcnt<0>();   // drain the loads issued past the range before the workgroup's LDS is released
+    wait_vmcnt<0>();   // drain the loads issued past the range before LDS is reused or released
+
+    // ---- merge the key groups: groups 1.. hand (m, l, O) to group 0 through LDS ----------------
+    // Each lane parks exactly the accumulator elements that the lane with the same position in
+    // group 0 owns, so the exchange is lane-to-lane (no transposition); 16-byte piece e of a lane
+    // sits at piece (e ^ n32') of its row to keep the banks apart.  One 32-row block at a time.
+    constexpr int kBlkBytes = 32 * 512;                         // one block of O: 32 rows x 128 fp32
+    constexpr int kLdsTotal = KG * NS * kStageBytes + (QLDS ? 32 * NRB * WR * kQRowBytes : 0);
+    constexpr int kMlBytes = WR * 64 * 8;                       // (m, l) per lane of the parked blocks
+    static_assert(KG == 1 || WR * kBlkBytes + kMlBytes <= kLdsTotal, "key-group merge staging must fit in LDS");
+    if (KG > 1) {
+        float *ml_park = reinterpret_cast<float *>(lds + WR * kBlkBytes);
+        unsigned char *blk = lds + wave * kBlkBytes + lane * 256;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+#pragma unroll
+            for (int g = 1; g < KG; ++g) {
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // ring, query fragments or the previous staging are free
+                if (kg == g && rb < nrb_live) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        f32x4 o = {oacc[rb][0][e], oacc[rb][1][e], oacc[rb][2][e], oacc[rb][3][e]};
+                        *reinterpret_cast<f32x4 *>(blk + ((e ^ (lane & 15)) << 4)) = o;
+                    }
+                    *reinterpret_cast<f32x2 *>(ml_park + (wave * 64 + lane) * 2) = f32x2{m_run[rb], l_run[rb]};
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                if (kg == 0 && rb < nrb_live) {
+                    const f32x2 ml_o = *reinterpret_cast<const f32x2 *>(ml_park + (wave * 64 + lane) * 2);
+                    const float m_all = fmaxf(m_run[rb], ml_o[0]);
+                    const float a0 = fast_exp2(m_run[rb] - m_all), ag = fast_exp2(ml_o[0] - m_all);
+                    l_run[rb] = fmaf(ag, ml_o[1], l_run[rb] * a0);
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const f32x4 o = *reinterpret_cast<const f32x4 *>(blk + ((e ^ (lane & 15)) << 4));
+#pragma unroll
+                        for (int cb = 0; cb < 4; ++cb) oacc[rb][cb][e] = fmaf(ag, o[cb], oacc[rb][cb][e] * a0);
+                    }
+                    m_run[rb] = m_all;
+                }
+            }
+        }
+    }
 
     // ---- write the partial: (m, l) and unnormalised O for every live row ----------------------
-    // O goes through LDS (the ring is free now) so that the stores cover whole 512-byte rows; a
-    // wavefront stages one 32-row block (16 KiB) at a time.  When the ring is smaller than one
-    // block per wavefront, the wavefronts take turns in groups of NS.
+    // O goes through LDS (free now) so that the stores cover whole 512-byte rows; a wavefront of
+    // key group 0 stages one 32-row block (16 KiB) at a time.  When LDS is smaller than one block
+    // per wavefront, the wavefronts take turns in groups of kSlots.
     const int n_part = p.n_split + 1;
     const int64_t part = ((int64_t)h * n_part + split) * p.n_rows_pad;
-    constexpr int kGroups = (WR + NS - 1) / NS;
+    constexpr int kSlots = kLdsTotal / kBlkBytes < WR ? kLdsTotal / kBlkBytes : WR;
+    constexpr int kGroups = (WR + kSlots - 1) / kSlots;
 #pragma unroll
     for (int grp = 0; grp < kGroups; ++grp) {
-        if (WR > 1) asm volatile("s_barrier" ::: "memory");   // the ring (or the previous group's staging) is free
-        if (kGroups > 1 && wave / NS != grp) continue;
-        unsigned char *region = lds + (kGroups > 1 ? wave % NS : wave) * (32 * 512);
+        if (WR * KG > 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS (or the previous group's staging) is free
+        if (kg != 0 || wave / kSlots != grp) continue;
+        unsigned char *region = lds + (wave % kSlots) * kBlkBytes;
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
             if (rb < nrb_live) {
@@ -431,36 +505,39 @@ verify_wide_kernel(const VerifyParams p)
                     f32x2 ml = {m_run[rb], l_tot};
                     *reinterpret_cast<f32x2 *>(p.ws_ml + (part + row_base + n32) * 2) = ml;
                 }
-                // element e of oacc[rb][cb] is output column 4*m + cb, m = hh*4 + 8*(e/4) + e%4:
-                // the four column blocks together make 16-byte piece m of row n32
+                // element e of oacc[rb][cb] is output column 32*cb + 4*hh + 8*(e/4) + e%4: four
+                // consecutive elements make 16-byte piece 8*cb + 2*(e/4) + hh of row n32
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    f32x4 o = {oacc[rb][0][e], oacc[rb][1][e], oacc[rb][2][e], oacc[rb][3][e]};
-                    const int m = hh * 4 + 8 * (e >> 2) + (e & 3);
-                    *reinterpret_cast<f32x4 *>(region + n32 * 512 + ((m ^ n32) << 4)) = o;
-                }
+                for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        f32x4 o = {oacc[rb][cb][4 * i], oacc[rb][cb][4 * i + 1], oacc[rb][cb][4 * i + 2], oacc[rb][cb][4 * i + 3]};
+                        const int m = 8 * cb + 2 * i + hh;
+                        *reinterpret_cast<f32x4 *>(region + n32 * 512 + ((m ^ n32) << 4)) = o;
+                    }
                 store_rows_from_lds<32>(region, p.n_rows - row_base, p.ws_o + (part + row_base) * kHeadDim, lane);
             }
         }
     }
 }
 
-template <int NRB, int WR, int NS, int OCC, bool QLDS, bool PIPE = false>
+template <int NRB, int WR, int KG, int NS, int OCC, bool QLDS, bool PIPE = false>
 hipError_t launch_one(const VerifyParams &p, hipStream_t stream)
 {
     constexpr int kRows = 32 * NRB * WR;
-    constexpr int lds_bytes = NS * kStageBytes + (QLDS ? kRows * kQRowBytes : 0);
+    constexpr int lds_bytes = KG * NS * kStageBytes + (QLDS ? kRows * kQRowBytes : 0);
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
+    static_assert(64 * WR * KG <= 1024, "workgroup size");
     if (p.rows_per_wg > kRows || p.rows_per_wg % 32 != 0) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (lds_bytes > 64 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(verify_wide_kernel<NRB, WR, NS, OCC, QLDS, PIPE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS, PIPE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(p.n_split + 1, p.n_kv_heads, (p.n_rows + p.rows_per_wg - 1) / p.rows_per_wg);
-    hipLaunchKernelGGL((verify_wide_kernel<NRB, WR, NS, OCC, QLDS, PIPE>), grid, dim3(64 * WR), lds_bytes, stream, p);
+    hipLaunchKernelGGL((verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS, PIPE>), grid, dim3(64 * WR * KG), lds_bytes, stream, p);
     return hipGetLastError();
 }
 
@@ -469,17 +546,19 @@ hipError_t launch_one(const VerifyParams &p, hipStream_t stream)
 hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t stream)
 {
     switch (kernel_id) {
-        case kWide_1x1: return launch_one<1, 1, 3, 2, false>(p, stream);
-        case kWide_1x1a: return launch_one<1, 1, 2, 2, false>(p, stream);
-        case kWide_1x1b: return launch_one<1, 1, 4, 2, false>(p, stream);
-        case kWide_1x1c: return launch_one<1, 1, 5, 2, false>(p, stream);
-        case kWide_1x2: return launch_one<1, 2, 4, 2, false>(p, stream);
-        case kWide_1x4: return launch_one<1, 4, 4, 2, false>(p, stream);
-        case kWide_1x4p: return launch_one<1, 4, 4, 2, false, true>(p, stream);
-        case kWide_2x4: return launch_one<2, 4, 6, 1, false>(p, stream);
-        case kWide_1x8: return launch_one<1, 8, 6, 2, false>(p, stream);
-        case kWide_3x4: return launch_one<3, 4, 6, 1, false>(p, stream);
-        case kWide_3x4q: return launch_one<3, 4, 3, 1, true>(p, stream);
+        case kWide_1x1: return launch_one<1, 1, 1, 3, 2, false>(p, stream);
+        case kWide_1x1b: return launch_one<1, 1, 1, 4, 2, false>(p, stream);
+        case kWide_1x2: return launch_one<1, 2, 1, 4, 2, false>(p, stream);
+        case kWide_1x4: return launch_one<1, 4, 1, 4, 2, false>(p, stream);
+        case kWide_1x4p: return launch_one<1, 4, 1, 8, 1, false, true>(p, stream);
+        case kWide_1x4k2: return launch_one<1, 4, 2, 3, 2, true>(p, stream);
+        case kWide_1x4k3: return launch_one<1, 4, 3, 2, 3, true>(p, stream);
+        case kWide_2x4: return launch_one<2, 4, 1, 6, 1, false>(p, stream);
+        case kWide_1x8: return launch_one<1, 8, 1, 6, 2, false>(p, stream);
+        case kWide_3x4: return launch_one<3, 4, 1, 6, 1, false>(p, stream);
+        case kWide_3x4q: return launch_one<3, 4, 1, 3, 1, true>(p, stream);
+        case kWide_1x10: return launch_one<1, 10, 1, 4, 3, true>(p, stream);
+        case kWide_1x12: return launch_one<1, 12, 1, 3, 3, true>(p, stream);
         default: return hipErrorInvalidValue;
     }
 }
