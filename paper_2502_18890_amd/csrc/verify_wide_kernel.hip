@@ -285,17 +285,49 @@ verify_wide_kernel(const VerifyParams p)
         constexpr int L = decltype(live_tag)::value;
         constexpr bool RAGGED = decltype(ragged_tag)::value;
 
-        // V^T operands: vt[cb][s] = column 32*cb + n32, keys 4*hh + 16*s + 8*(e/4) + e%4 (e = 0..7)
+        // V^T operands: vt[cb][s] = column 32*cb + n32, keys 4*hh + 16*s + 8*(e/4) + e%4 (e = 0..7).
+        // The sixteen transposed reads and their wait are one asm block: issued through the
+        // compiler's builtin, each would be preceded by a wait for ALL outstanding tile loads
+        // (LDS written by buffer_load ... lds is tracked by vmcnt and the builtin carries no alias
+        // information), i.e. for the whole prefetched ring.  The stage read here was completed by
+        // the vmcnt wait + barrier at the top of the step.  The block sits right behind the S^T
+        // products, whose execution covers its LDS latency.
         bf16x8 vt[4][2];
+        {
+            const uint32_t sbase = (uint32_t)(uintptr_t)stage;   // low half of a generic LDS address = LDS offset
+            const uint32_t a0 = sbase + voff[0], a1 = sbase + voff[1], a2 = sbase + voff[2], a3 = sbase + voff[3];
+            u32x2 r[16];
+            asm volatile(
+                "ds_read_b64_tr_b16 %0, %16\n\t"
+                "ds_read_b64_tr_b16 %1, %16 offset:2048\n\t"
+                "ds_read_b64_tr_b16 %2, %16 offset:4096\n\t"
+                "ds_read_b64_tr_b16 %3, %16 offset:6144\n\t"
+                "ds_read_b64_tr_b16 %4, %17\n\t"
+                "ds_read_b64_tr_b16 %5, %17 offset:2048\n\t"
+                "ds_read_b64_tr_b16 %6, %17 offset:4096\n\t"
+                "ds_read_b64_tr_b16 %7, %17 offset:6144\n\t"
+                "ds_read_b64_tr_b16 %8, %18\n\t"
+                "ds_read_b64_tr_b16 %9, %18 offset:2048\n\t"
+                "ds_read_b64_tr_b16 %10, %18 offset:4096\n\t"
+                "ds_read_b64_tr_b16 %11, %18 offset:6144\n\t"
+                "ds_read_b64_tr_b16 %12, %19\n\t"
+                "ds_read_b64_tr_b16 %13, %19 offset:2048\n\t"
+                "ds_read_b64_tr_b16 %14, %19 offset:4096\n\t"
+                "ds_read_b64_tr_b16 %15, %19 offset:6144\n\t"
+                "s_waitcnt lgkmcnt(0)"
+                : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7]),
+                  "=&v"(r[8]), "=&v"(r[9]), "=&v"(r[10]), "=&v"(r[11]), "=&v"(r[12]), "=&v"(r[13]), "=&v"(r[14]), "=&v"(r[15])
+                : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+                : "memory");
+            // r[4*cb + 2*s + x]: keys 16*s + 8*x + 4*hh + (0..3) of column block cb
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
+            for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(stage + voff[cb] + (16 * s) * 256));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(stage + voff[cb] + (16 * s + 8) * 256));
-                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                vt[cb][s] = __builtin_bit_cast(bf16x8, both);
-            }
+                for (int s = 0; s < 2; ++s) {
+                    const u32x4 both = {r[4 * cb + 2 * s][0], r[4 * cb + 2 * s][1], r[4 * cb + 2 * s + 1][0], r[4 * cb + 2 * s + 1][1]};
+                    vt[cb][s] = __builtin_bit_cast(bf16x8, both);
+                }
+        }
 
         // Row maxima (raw logits; scale > 0 commutes with max).  Element e of sacc is key
         // hh*4 + 8*(e/4) + e%4 of the tile, for query row n32.  m_run is a reference point, not
