@@ -186,6 +186,11 @@ def main():
     alg_bytes = (hkv * n * cfg.head_dim * 2 * 2 + t * hkv * cfg.head_dim * 2 * 2 + t * hq * cfg.head_dim * 2
                  + t * hq * cfg.head_dim * 4)
     achieved = alg_bytes / (kern_us * 1e-6) / 1e9
+    # the same launch against the matrix-core roofline: algorithmic flops = QK^T and PV once each,
+    # 4*g*T*d flops per cached or tree key and KV head (the second, low-order PV product that keeps
+    # the weights' precision is an implementation cost and is not counted)
+    alg_flops = 4.0 * cfg.group * t * cfg.head_dim * (n + t) * hkv
+    kernel_name = "verify_dma_kernel (16x16x32 MFMA)" if cfg.group * t <= 32 else "verify_wide_kernel (32x32x16 MFMA)"
 
     us_per_layer_step = ms_per_step * 1e3 / n_layers
     res = {
@@ -201,11 +206,14 @@ def main():
         "cache_maintenance_us_per_layer": {k: round(v, 3) for k, v in maint.items()},
         "verify_call_gbs": round(alg_bytes / (parts["verify"] * 1e-6) / 1e9, 1),
         "wall_s_timed_region": round(wall, 3),
-        "roofline": {"kernel": "verify_dma_kernel (split-K tree-verify attention, split kernel)", "bound": "hbm",
+        "roofline": {"kernel": kernel_name + ", split kernel of the tree-verify pass", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": measured_traffic(cfg.name) if n == cfg.n_tokens else None,
                      "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": round(kern_us, 3)},
+        "roofline_mfma": {"bound": "mfma", "achieved": round(alg_flops / (kern_us * 1e-6) / 1e12, 2), "peak": 2500.0,
+                          "unit": "TFLOP/s", "frac": round(alg_flops / (kern_us * 1e-6) / 2.5e15, 4),
+                          "algorithmic_flops_per_launch": alg_flops, "flops_per_byte": round(alg_flops / alg_bytes, 1)},
     }
     if args.calibrate_copy:
         a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
