@@ -153,8 +153,9 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
                         size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
- * Cache maintenance around the attention calls (Alg. 1: "update C_full", "Evict C_p",
- * "Dynamic KV Cache Update"; Sec. 3.3 "Dynamic KV Cache Updates").
+ * Cache maintenance around the attention calls (Alg. 1: the update of C_full and the eviction
+ * inside C_p at the end of each iteration, the "Dynamic KV Cache Update" step; Sec. 3.3
+ * "Dynamic KV Cache Updates").
  * ------------------------------------------------------------------------------------- */
 
 /*
@@ -172,7 +173,8 @@ int ts_append_accepted(const ts_kv_view *kv, const void *k_tree, const void *v_t
                        const int32_t *accepted, int n_accepted, void *stream);
 
 /*
- * When the partial cache must be rebuilt (Alg. 1, "if (|C_full| - e) > |B| - |S|"; Sec. 3.3:
+ * When the partial cache must be rebuilt (Alg. 1, the condition guarding the "Dynamic KV Cache
+ * Update" step: more than |B| - |S| tokens were added since the last rebuild at size e; Sec. 3.3:
  * new tokens replace the least important entries of C_p from position |B|-1 towards |S|, and
  * once they would pass |S| the importance scores are recomputed).  All sizes in tokens.
  * Returns 1 if a rebuild is due, 0 if not, TS_ERR_SHAPE for negative or inconsistent sizes.

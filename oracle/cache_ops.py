@@ -4,7 +4,8 @@ Plain numpy, one obvious loop or indexing expression per definition; bf16 values
 patterns (copies move the bits untouched, sums widen them exactly to float64).  Shares nothing
 with the GPU library.  Passages followed:
   append_accepted      Alg. 1, last step of the loop: C_full is updated with the accepted tokens.
-  refresh_due          Alg. 1, "if (|C_full| - e) > |B| - |S|".
+  refresh_due          Alg. 1, the condition that guards the "Dynamic KV Cache Update" step: more than |B| - |S|
+                       tokens were added since the last rebuild.
   chunk_list_admit     Sec. 3.3 "Dynamic KV Cache Updates": new tokens replace the least important
                        entries of C_p, from position |B|-1 towards |S| (here one chunk per entry).
   gather_chunks        Alg. 1: C_p = {C_full[0:|S|], Top-K(C_full)} as a buffer of its own.

@@ -1,5 +1,5 @@
 // Top-k chunk selection for the partial cache (Alg. 1: C_p = first |S| entries plus the
-// |B|-|S| most important others, "ordered by decreasing importance", Sec. 3.3), for gfx950.
+// |B|-|S| most important others, from most to least important, Sec. 3.3), for gfx950.
 //
 // One workgroup per KV head.  Every candidate chunk gets a 64-bit key: high word = its score
 // mapped to an unsigned integer that orders like the float (NaN lowest, -0 == +0), low word =
