@@ -1,0 +1,69 @@
+"""CPU oracle for the penalized sampling step -- TEST INFRASTRUCTURE ONLY.
+
+Plain numpy in float64; shares nothing with the GPU library.  Passages followed:
+  penalized_probs   Sec. 3.4 "Contextual Penalty", Eq. 3: softmax of l_i / (t * I_i) with I_i = theta for
+                    tokens that occur among the W most recent generated tokens and 1 otherwise.
+  pool_threshold    App. D: the sampling pools of min-p (probability >= p_base * p_max) and top-p (the
+                    most probable tokens whose mass reaches p), both written as "probability >= tau".
+  sample            App. D: the next token is drawn from the pool with the renormalised probabilities;
+                    here by inverting the pool's cumulative distribution, taken in order of token id,
+                    at a uniform number that is passed in.
+Pins: tests/test_sampling_pins.py.
+"""
+import numpy as np
+
+FULL, MIN_P, TOP_P = 0, 1, 2
+
+
+def penalized_probs(logits, window, temperature, theta):
+    """logits [R, V] (any float dtype, widened), window: iterable of token ids -> float64 [R, V]."""
+    l = np.asarray(logits, dtype=np.float64)
+    indicator = np.ones(l.shape[1], dtype=np.float64)
+    for tok in window:
+        indicator[int(tok)] = theta
+    x = l / (temperature * indicator)
+    x = x - x.max(axis=1, keepdims=True)
+    e = np.exp(x)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def pool_threshold(p_row, method, param):
+    """Probability threshold tau of the pool {v : p[v] >= tau} for one row.
+
+    The product p_base * p_max and the comparison are taken in float32 when the row is float32
+    (the precision in which the GPU takes the same decision)."""
+    p = np.asarray(p_row)
+    if method == FULL:
+        return p.dtype.type(0)
+    if method == MIN_P:
+        return p.dtype.type(param) * p.max()
+    if method == TOP_P:
+        # smallest set of most probable tokens whose mass reaches `param`: walk the tokens in order of
+        # decreasing probability; tokens tied with the last one taken are all kept
+        order = np.argsort(-p.astype(np.float64), kind="stable")
+        mass = 0.0
+        tau = p[order[-1]]
+        for v in order:
+            mass += float(p[v])
+            if mass >= param:
+                tau = p[v]
+                break
+        return tau
+    raise ValueError(method)
+
+
+def sample(p_row, method, param, u):
+    """-> (token, pool_mass, margin): margin = distance of u*pool_mass to the nearest step of the
+    pool's cumulative distribution, relative to pool_mass (how decisive the draw was)."""
+    p = np.asarray(p_row)
+    tau = pool_threshold(p, method, param)
+    in_pool = p >= tau
+    w = np.where(in_pool, p.astype(np.float64), 0.0)
+    cdf = np.cumsum(w)
+    mass = cdf[-1]
+    target = float(u) * mass
+    tok = int(np.searchsorted(cdf, target, side="right"))     # first id whose cumulative mass exceeds the target
+    tok = min(tok, int(np.nonzero(in_pool)[0][-1]))
+    steps = cdf[in_pool]
+    margin = float(np.min(np.abs(steps - target))) / mass
+    return tok, mass, margin
