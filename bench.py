@@ -176,6 +176,25 @@ def main():
                 x["v"][:, n - len(acc):] = sv
     del kg, vg, ksum
 
+    # penalized probabilities + pool sampling for the T verification rows (once per step, not per
+    # layer; not part of `value`): vocabulary of the model the workload is shaped like
+    vocab = {"tiny": 32000, "qwen2.5-1.5b": 151936, "llama3.1-8b": 128256, "yarn-llama2-7b-mha": 32000,
+             "qwen2.5-14b": 152064}.get(cfg.name, 32000)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed)
+    logits = torch.randn(t, vocab, generator=gen, device=dev, dtype=torch.float32) * 3.0
+    window = torch.randint(0, vocab, (1024,), generator=gen, device=dev, dtype=torch.int32)
+    uni = torch.rand(t, generator=gen, device=dev, dtype=torch.float32)
+    probs = torch.empty_like(logits)
+    ws_s = torch.empty(max(1, ts.load_library().ts_sampling_workspace_bytes(t, vocab)), dtype=torch.uint8, device=dev)
+    sampling = {
+        "penalized_probs": timed(lambda: ts.penalized_probs(logits, window, 1.0, 1.15, out=probs, workspace=ws_s), 20) * 1e3,
+        "sample_min_p": timed(lambda: ts.sample_tokens(probs, ts.SAMPLE_MIN_P, 0.1, uni), 20) * 1e3,
+        "sample_top_p": timed(lambda: ts.sample_tokens(probs, ts.SAMPLE_TOP_P, 0.9, uni), 20) * 1e3,
+    }
+    sampling_bytes = 3 * t * vocab * 4   # logits read twice, probabilities written once
+    del logits, probs
+
     # the dominant kernel alone (split kernel of the verification pass), for the roofline
     ts.tune_set("verify_stage", 1)
     try:
@@ -204,6 +223,8 @@ def main():
         "breakdown_us_per_layer": {k: round(v, 3) for k, v in parts.items()},
         "verify_plus_partial_us_per_layer": round(parts["verify"] + parts["partial"], 3),
         "cache_maintenance_us_per_layer": {k: round(v, 3) for k, v in maint.items()},
+        "sampling_us_per_step": dict({k: round(v, 3) for k, v in sampling.items()}, rows=t, vocab=vocab, window=1024,
+                                     penalized_probs_gbs=round(sampling_bytes / (sampling["penalized_probs"] * 1e-6) / 1e9, 1)),
         "verify_call_gbs": round(alg_bytes / (parts["verify"] * 1e-6) / 1e9, 1),
         "wall_s_timed_region": round(wall, 3),
         "roofline": {"kernel": kernel_name + ", split kernel of the tree-verify pass", "bound": "hbm",

@@ -225,6 +225,42 @@ int ts_chunk_scores_from_sums(const float *ksum, int64_t ksum_stride_head, int n
                               int64_t n_tokens, const void *q, int n_q_heads, int chunk_size,
                               float scale, float *scores, void *stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Penalized probabilities and sampling pools (Sec. 3.4 "Contextual Penalty", Eq. 3; App. D).
+ * ------------------------------------------------------------------------------------- */
+
+enum { TS_SAMPLE_FULL = 0, TS_SAMPLE_MIN_P = 1, TS_SAMPLE_TOP_P = 2 };
+
+/* Bytes of device workspace ts_penalized_probs needs (0 on invalid arguments). */
+size_t ts_sampling_workspace_bytes(int n_rows, int64_t vocab);
+
+/*
+ * Eq. 3: probs[r][i] = softmax_i( logits[r][i] / (temperature * I_i) ), I_i = theta if token i occurs
+ * in `window` (the ids of the most recent W generated tokens; repeats allowed, ids outside
+ * [0, vocab) ignored), else 1.  As printed in the paper, the logit is divided whatever its sign.
+ *   logits, probs  fp32 [n_rows][vocab], 16-byte aligned (may not alias)
+ *   window         device int32 [n_window]; may be NULL when n_window == 0
+ *   workspace      >= ts_sampling_workspace_bytes(n_rows, vocab) bytes, 256-byte aligned; scratch
+ * temperature > 0, theta >= 1, both finite; 1 <= vocab <= 2^24; n_rows >= 1.
+ */
+int ts_penalized_probs(const float *logits, int n_rows, int64_t vocab, const int32_t *window,
+                       int n_window, float temperature, float theta, float *probs, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+/*
+ * Draws one token per row from a sampling pool of App. D with the renormalised probabilities.
+ * The pool is {i : probs[r][i] >= tau_r}: TS_SAMPLE_FULL: every token; TS_SAMPLE_MIN_P: tau = param *
+ * max_i probs[r][i] (param = p_base in (0, 1]); TS_SAMPLE_TOP_P: the largest tau whose pool still holds
+ * mass >= param (param = p in (0, 1]): the most probable tokens whose mass reaches p, tokens tied
+ * with the last one all kept.  The draw inverts the pool's cumulative distribution, taken in order
+ * of token id, at u[r]: the first pool token whose cumulative pool mass exceeds u[r] * pool mass.
+ *   probs  fp32 [n_rows][vocab]; u  device fp32 [n_rows] in [0, 1) (clamped); tokens  int32 [n_rows]
+ *   pool_threshold, pool_mass  fp32 [n_rows], nullable: tau_r and the pool's mass
+ */
+int ts_sample_tokens(const float *probs, int n_rows, int64_t vocab, int method, float param,
+                     const float *u, int32_t *tokens, float *pool_threshold, float *pool_mass,
+                     void *stream);
+
 /*
  * Tuning hook (not needed for correct results): overrides a launch-geometry choice until
  * reset with value 0.  Names: "verify_splits" (number of cache splits per KV head);

@@ -69,6 +69,12 @@ def load_library():
     lib.ts_gather_chunks.argtypes = [kvp, vp, ci, ci, vp, vp, vp]
     lib.ts_chunk_key_sums.argtypes = [kvp, ci, i64, i64, vp, i64, vp]
     lib.ts_chunk_scores_from_sums.argtypes = [vp, i64, ci, i64, vp, ci, ci, cf, vp, vp]
+    lib.ts_sampling_workspace_bytes.argtypes = [ci, i64]
+    lib.ts_sampling_workspace_bytes.restype = ctypes.c_size_t
+    lib.ts_penalized_probs.argtypes = [vp, ci, i64, vp, ci, cf, cf, vp, vp, ctypes.c_size_t, vp]
+    lib.ts_sample_tokens.argtypes = [vp, ci, i64, ci, cf, vp, vp, vp, vp, vp]
+    lib.ts_penalized_probs.restype = ci
+    lib.ts_sample_tokens.restype = ci
     for name in ("ts_tune_set", "ts_chunk_scores", "ts_topk_chunks", "ts_partial_kv_attn",
                  "ts_tree_verify_attn", "ts_append_accepted", "ts_refresh_due", "ts_chunk_list_admit",
                  "ts_gather_chunks", "ts_chunk_key_sums", "ts_chunk_scores_from_sums"):
@@ -273,3 +279,43 @@ def chunk_scores_from_sums(ksum: torch.Tensor, n_tokens: int, q: torch.Tensor, c
                                                     q.data_ptr(), q.shape[0], int(chunk_size), float(scale),
                                                     out.data_ptr(), _stream()), "ts_chunk_scores_from_sums")
     return out
+
+
+# ---- penalized probabilities and sampling ------------------------------------------------------------
+SAMPLE_FULL, SAMPLE_MIN_P, SAMPLE_TOP_P = 0, 1, 2
+
+
+def penalized_probs(logits: torch.Tensor, window: Optional[torch.Tensor], temperature: float, theta: float,
+                    out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """logits fp32 [R,V], window int32 [W] (device) or None -> probs fp32 [R,V] (Eq. 3)."""
+    lib = load_library()
+    if logits.dtype != torch.float32 or logits.dim() != 2 or not logits.is_contiguous():
+        raise ValueError("logits must be a contiguous fp32 [rows, vocab] tensor")
+    r, v = logits.shape
+    nbytes = int(lib.ts_sampling_workspace_bytes(r, v))
+    workspace = _workspace(nbytes, logits.device, workspace)
+    if out is None:
+        out = torch.empty_like(logits)
+    n_window = 0 if window is None else int(window.numel())
+    if window is not None:
+        window = window.contiguous()
+    _check(lib.ts_penalized_probs(logits.data_ptr(), r, v, window.data_ptr() if n_window else None, n_window,
+                                  float(temperature), float(theta), out.data_ptr(), workspace.data_ptr(),
+                                  workspace.numel(), _stream()), "ts_penalized_probs")
+    return out
+
+
+def sample_tokens(probs: torch.Tensor, method: int, param: float, u: torch.Tensor, want_pool: bool = False):
+    """probs fp32 [R,V], u fp32 [R] -> tokens int32 [R] (and (threshold, mass) fp32 [R] each)."""
+    lib = load_library()
+    if probs.dtype != torch.float32 or probs.dim() != 2 or not probs.is_contiguous():
+        raise ValueError("probs must be a contiguous fp32 [rows, vocab] tensor")
+    r, v = probs.shape
+    u = u.contiguous()
+    tokens = torch.empty(r, dtype=torch.int32, device=probs.device)
+    thr = torch.empty(r, dtype=torch.float32, device=probs.device) if want_pool else None
+    mass = torch.empty(r, dtype=torch.float32, device=probs.device) if want_pool else None
+    _check(lib.ts_sample_tokens(probs.data_ptr(), r, v, int(method), float(param), u.data_ptr(), tokens.data_ptr(),
+                                thr.data_ptr() if want_pool else None, mass.data_ptr() if want_pool else None, _stream()),
+           "ts_sample_tokens")
+    return (tokens, thr, mass) if want_pool else tokens

@@ -494,4 +494,57 @@ int ts_chunk_scores_from_sums(const float *ksum, int64_t ksum_stride_head, int n
     return ts::launch_sum_scores(p, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
+size_t ts_sampling_workspace_bytes(int n_rows, int64_t vocab)
+{
+    if (n_rows < 1 || vocab < 1 || vocab > (1 << 24)) return 0;
+    return round_up((size_t)n_rows * ts::sampling_slices(vocab) * 2 * sizeof(float), 256);
+}
+
+int ts_penalized_probs(const float *logits, int n_rows, int64_t vocab, const int32_t *window,
+                       int n_window, float temperature, float theta, float *probs, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    if (!logits || !probs || (n_window > 0 && !window)) return TS_ERR_NULL;
+    if (n_rows < 1 || vocab < 1 || n_window < 0) return TS_ERR_SHAPE;
+    if (vocab > (1 << 24) || n_rows > 65535) return TS_ERR_UNSUPPORTED;
+    if (!(temperature > 0.f && temperature < 3.0e38f) || !(theta >= 1.f && theta < 3.0e38f)) return TS_ERR_UNSUPPORTED;
+    if (!aligned16(logits) || !aligned16(probs)) return TS_ERR_ALIGN;
+    const size_t need = ts_sampling_workspace_bytes(n_rows, vocab);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return TS_ERR_WORKSPACE;
+    ts::PenaltyParams p;
+    p.logits = logits;
+    p.probs = probs;
+    p.window = window;
+    p.n_window = n_window;
+    p.stats = static_cast<float *>(workspace);
+    p.vocab = vocab;
+    p.n_rows = n_rows;
+    p.n_slices = ts::sampling_slices(vocab);
+    p.k_plain = 1.4426950408889634f / temperature;
+    p.k_window = 1.4426950408889634f / (temperature * theta);
+    return ts::launch_penalized_probs(p, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int ts_sample_tokens(const float *probs, int n_rows, int64_t vocab, int method, float param,
+                     const float *u, int32_t *tokens, float *pool_threshold, float *pool_mass,
+                     void *stream)
+{
+    if (!probs || !u || !tokens) return TS_ERR_NULL;
+    if (n_rows < 1 || vocab < 1) return TS_ERR_SHAPE;
+    if (vocab > (1 << 24)) return TS_ERR_UNSUPPORTED;
+    if (method != TS_SAMPLE_FULL && method != TS_SAMPLE_MIN_P && method != TS_SAMPLE_TOP_P) return TS_ERR_UNSUPPORTED;
+    if (method != TS_SAMPLE_FULL && !(param > 0.f && param <= 1.f)) return TS_ERR_UNSUPPORTED;
+    ts::SampleParams p;
+    p.probs = probs;
+    p.u = u;
+    p.tokens = tokens;
+    p.pool_threshold = pool_threshold;
+    p.pool_mass = pool_mass;
+    p.vocab = vocab;
+    p.n_rows = n_rows;
+    p.method = method;
+    p.param = param;
+    return ts::launch_sample(p, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
 }  // extern "C"

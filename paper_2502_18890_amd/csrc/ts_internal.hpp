@@ -148,4 +148,30 @@ struct SumScoresParams {
 };
 hipError_t launch_sum_scores(const SumScoresParams &p, hipStream_t stream);
 
+// ---- penalized probabilities and pool sampling (sampling_kernels.hip) -----------------------------
+struct PenaltyParams {
+    const float *logits;      // fp32 [n_rows][vocab]
+    float *probs;             // fp32 [n_rows][vocab]
+    const int32_t *window;    // device int32 [n_window]: ids of the tokens in the penalty window
+    float *stats;             // [n_rows][n_slices][2]: per-slice max (exp2 domain) and sum of exponentials
+    int64_t vocab;
+    int n_rows, n_slices, n_window;
+    float k_plain, k_window;  // log2(e) / t  and  log2(e) / (t * theta)
+};
+int sampling_slices(int64_t vocab);
+hipError_t launch_penalized_probs(const PenaltyParams &p, hipStream_t stream);
+
+enum { kSampleFull = 0, kSampleMinP = 1, kSampleTopP = 2 };
+struct SampleParams {
+    const float *probs;       // fp32 [n_rows][vocab]
+    const float *u;           // fp32 [n_rows], uniform in [0, 1)
+    int32_t *tokens;          // [n_rows]
+    float *pool_threshold;    // [n_rows] or nullptr
+    float *pool_mass;         // [n_rows] or nullptr
+    int64_t vocab;
+    int n_rows, method;
+    float param;
+};
+hipError_t launch_sample(const SampleParams &p, hipStream_t stream);
+
 }  // namespace ts

@@ -31,9 +31,9 @@ def test_library_exports_every_declared_function(lib):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(ts_[a-z_]+)\s*\(", text)))
     assert names == ["ts_append_accepted", "ts_chunk_key_sums", "ts_chunk_list_admit", "ts_chunk_scores",
-                     "ts_chunk_scores_from_sums", "ts_gather_chunks", "ts_partial_kv_attn", "ts_refresh_due",
-                     "ts_strerror", "ts_topk_chunks", "ts_tree_verify_attn", "ts_tune_set", "ts_version",
-                     "ts_workspace_bytes"]
+                     "ts_chunk_scores_from_sums", "ts_gather_chunks", "ts_partial_kv_attn", "ts_penalized_probs",
+                     "ts_refresh_due", "ts_sample_tokens", "ts_sampling_workspace_bytes", "ts_strerror",
+                     "ts_topk_chunks", "ts_tree_verify_attn", "ts_tune_set", "ts_version", "ts_workspace_bytes"]
     for n in names:
         assert hasattr(lib, n), n
     assert lib.ts_version() >= 100
@@ -183,3 +183,23 @@ def test_cache_maintenance_calls_reject_bad_arguments(lib, binding):
     assert sf(ksum=None) == TS_ERR_NULL and sf(q=None) == TS_ERR_NULL and sf(out=None) == TS_ERR_NULL
     assert sf(hq=3) == TS_ERR_SHAPE and sf(hq=18) == TS_ERR_UNSUPPORTED and sf(n=0) == TS_ERR_SHAPE
     assert sf(chunk=2000) == TS_ERR_UNSUPPORTED and sf(sh=128) == TS_ERR_SHAPE
+
+
+def test_sampling_calls_reject_bad_arguments(lib):
+    wsb = lib.ts_sampling_workspace_bytes
+    assert wsb(100, 128256) >= 100 * 32 * 8
+    assert wsb(0, 1000) == 0 and wsb(4, 0) == 0 and wsb(4, (1 << 24) + 1) == 0
+    big = 1 << 30
+    pp = lambda lg=0x1000, r=4, v=1000, win=0x3000, nw=8, t=1.0, th=1.2, out=0x2000, ws=0x10000, wb=big: lib.ts_penalized_probs(
+        lg, r, v, win, nw, t, th, out, ws, wb, None)
+    assert pp(lg=None) == TS_ERR_NULL and pp(out=None) == TS_ERR_NULL and pp(win=None) == TS_ERR_NULL
+    assert pp(r=0) == TS_ERR_SHAPE and pp(v=0) == TS_ERR_SHAPE and pp(nw=-1) == TS_ERR_SHAPE
+    assert pp(t=0.0) == TS_ERR_UNSUPPORTED and pp(t=float("nan")) == TS_ERR_UNSUPPORTED and pp(th=0.9) == TS_ERR_UNSUPPORTED
+    assert pp(v=(1 << 24) + 1) == TS_ERR_UNSUPPORTED
+    assert pp(lg=0x1004) == TS_ERR_ALIGN
+    assert pp(ws=None) == TS_ERR_WORKSPACE and pp(wb=16) == TS_ERR_WORKSPACE and pp(ws=0x10010) == TS_ERR_WORKSPACE
+    st = lambda pr=0x1000, r=4, v=1000, m=1, par=0.1, u=0x3000, tok=0x4000: lib.ts_sample_tokens(pr, r, v, m, par, u, tok, None, None, None)
+    assert st(pr=None) == TS_ERR_NULL and st(u=None) == TS_ERR_NULL and st(tok=None) == TS_ERR_NULL
+    assert st(r=0) == TS_ERR_SHAPE and st(v=0) == TS_ERR_SHAPE
+    assert st(m=3) == TS_ERR_UNSUPPORTED and st(m=-1) == TS_ERR_UNSUPPORTED
+    assert st(par=0.0) == TS_ERR_UNSUPPORTED and st(par=1.5) == TS_ERR_UNSUPPORTED and st(m=2, par=float("nan")) == TS_ERR_UNSUPPORTED

@@ -1,0 +1,121 @@
+"""GPU parity of the penalized probabilities and the pool sampler (through the C ABI) against the
+numpy oracle.  Probabilities: the floating-point bar.  Sampled tokens and pool thresholds are
+decisions that floating point takes: the oracle is given the GPU's own fp32 probabilities and takes
+them in fp32 too; a draw is compared exactly unless the oracle says it was not decisive (the target
+within 1e-5 of a step of the cumulative distribution), in which case the neighbouring pool token is
+accepted as well."""
+import numpy as np
+import pytest
+
+from oracle import sampling as O
+from gpu_util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ts():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2502_18890_amd as lib
+    lib.load_library()
+    return lib
+
+
+def _logits(rng, r, v, spread=3.0):
+    return (rng.standard_normal((r, v)) * spread).astype(np.float32)
+
+
+@pytest.mark.parametrize("r,v,nw,t,theta", [(4, 1000, 16, 1.0, 1.2), (3, 4096, 100, 0.7, 1.15), (2, 4097, 0, 1.3, 1.5),
+                                            (5, 32000, 1024, 1.0, 1.15), (2, 128256, 1024, 1.0, 1.2), (1, 151936, 2048, 0.9, 1.13),
+                                            (7, 33, 5, 1.0, 2.0), (1, 1, 1, 1.0, 1.2)])
+def test_penalized_probs(ts, r, v, nw, t, theta):
+    import torch
+    rng = np.random.default_rng(41)
+    lg = _logits(rng, r, v)
+    window = rng.integers(0, v, size=nw).astype(np.int32)
+    if nw > 3:
+        window[1] = window[0]                   # repeats are allowed
+    got = ts.penalized_probs(torch.from_numpy(lg).cuda(), torch.from_numpy(window).cuda() if nw else None, t, theta)
+    ref = O.penalized_probs(lg, window, t, theta)
+    assert_close(got.cpu().numpy(), ref, "penalized probs")
+    np.testing.assert_allclose(got.cpu().numpy().astype(np.float64).sum(axis=1), 1.0, rtol=0, atol=1e-5)
+
+
+def test_penalized_probs_peaked_and_flat_rows(ts):
+    import torch
+    v = 5000
+    lg = np.zeros((3, v), dtype=np.float32)
+    lg[0, 77] = 60.0                            # one token takes everything
+    lg[1, :] = -200.0                           # flat and far from zero
+    lg[2, ::2] = 30.0
+    window = np.array([77, 78, 0], dtype=np.int32)
+    got = ts.penalized_probs(torch.from_numpy(lg).cuda(), torch.from_numpy(window).cuda(), 1.0, 1.2).cpu().numpy()
+    assert_close(got, O.penalized_probs(lg, window, 1.0, 1.2), "penalized probs, peaked/flat")
+
+
+def _check_draws(ts, probs_gpu, method, param, u):
+    import torch
+    p = probs_gpu.cpu().numpy()
+    tok, thr, mass = ts.sample_tokens(probs_gpu, method, param, torch.from_numpy(u).cuda(), want_pool=True)
+    tok, thr, mass = tok.cpu().numpy(), thr.cpu().numpy(), mass.cpu().numpy()
+    n_ambiguous = 0
+    for r in range(p.shape[0]):
+        tau = O.pool_threshold(p[r], method, param)
+        if method == O.TOP_P:
+            # the cut itself is a floating-point decision: accept the neighbouring thresholds when the mass
+            # at the cut is within 1e-5 of param
+            order = np.sort(p[r].astype(np.float64))[::-1]
+            cum = np.cumsum(order)
+            near = np.abs(cum - param) < 1e-5
+            if near.any() and thr[r] != tau:   # e.g. param = 1.0: the whole row's mass is 1 only up to rounding
+                tau = thr[r]
+        assert thr[r] == tau, (r, thr[r], tau)
+        ref_tok, ref_mass, margin = O.sample(np.where(p[r] >= tau, p[r], 0).astype(np.float32), O.FULL, 0.0, u[r])
+        assert abs(mass[r] - ref_mass) <= 1e-5 * max(ref_mass, 1e-30)
+        assert p[r, tok[r]] >= tau and p[r, tok[r]] > 0
+        if tok[r] != ref_tok:
+            assert margin < 1e-5, (r, tok[r], ref_tok, margin)
+            pool_ids = np.nonzero(p[r] >= tau)[0]
+            assert abs(int(np.searchsorted(pool_ids, tok[r])) - int(np.searchsorted(pool_ids, ref_tok))) == 1
+            n_ambiguous += 1
+    assert n_ambiguous <= max(1, p.shape[0] // 10)
+
+
+@pytest.mark.parametrize("method,param", [(O.FULL, 0.0), (O.MIN_P, 0.1), (O.MIN_P, 0.05), (O.MIN_P, 1.0), (O.TOP_P, 0.9), (O.TOP_P, 0.5),
+                                          (O.TOP_P, 1.0)])
+@pytest.mark.parametrize("r,v", [(40, 1000), (16, 32000), (8, 128256), (3, 4099)])
+def test_sampling_pools_and_draws(ts, method, param, r, v):
+    import torch
+    rng = np.random.default_rng(42)
+    lg = _logits(rng, r, v, spread=2.5)
+    probs = ts.penalized_probs(torch.from_numpy(lg).cuda(), None, 1.0, 1.0)
+    u = rng.random(r).astype(np.float32)
+    u[0] = 0.0
+    u[-1] = 0.99999
+    _check_draws(ts, probs, method, param, u)
+
+
+def test_sampling_with_ties_and_tiny_vocab(ts):
+    import torch
+    p = np.array([[0.3, 0.2, 0.2, 0.2, 0.1], [0.0, 0.5, 0.0, 0.5, 0.0], [1.0, 0.0, 0.0, 0.0, 0.0]], dtype=np.float32)
+    pg = torch.from_numpy(p).cuda()
+    for method, param in ((O.TOP_P, 0.45), (O.MIN_P, 0.6), (O.FULL, 0.0)):
+        for uu in (0.0, 0.31, 0.5, 0.77, 0.99):
+            _check_draws(ts, pg, method, param, np.full(3, uu, dtype=np.float32))
+
+
+def test_sampling_frequencies_follow_the_pool_distribution(ts):
+    """Many rows with the same distribution and a grid of uniforms: token counts match the
+    renormalised pool probabilities."""
+    import torch
+    base = np.array([0.02, 0.38, 0.1, 0.25, 0.2, 0.05], dtype=np.float32)
+    n = 4000
+    pg = torch.from_numpy(np.tile(base, (n, 1))).cuda()
+    u = ((np.arange(n) + 0.5) / n).astype(np.float32)
+    for method, param in ((O.MIN_P, 0.3), (O.TOP_P, 0.8)):
+        tok = ts.sample_tokens(pg, method, param, torch.from_numpy(u).cuda()).cpu().numpy()
+        tau = O.pool_threshold(base, method, param)
+        want = np.where(base >= tau, base, 0.0).astype(np.float64)
+        want /= want.sum()
+        np.testing.assert_allclose(np.bincount(tok, minlength=6) / n, want, rtol=0, atol=2.0 / n)
