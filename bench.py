@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layer caches (0 = the config's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-loops", type=int, default=2, help="extra sweeps of the verify kernel alone for the roofline figure")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one whole step (all layers) in a HIP graph and time its replays instead of eager launches")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run an elementwise kernel that reads 1 GiB and writes 1 GiB (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -140,8 +142,19 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:   # the calls allocate nothing and never synchronise, so a step can be captured as it is
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        torch.cuda.synchronize()
+        run_step = graph.replay
+        run_step()
+        torch.cuda.synchronize()
     wall0 = time.perf_counter()
-    ms_per_step = timed(step, args.steps)
+    ms_per_step = timed(run_step, args.steps)
     wall = time.perf_counter() - wall0
 
     # per-function breakdown (each swept over all layers, same rotation)
@@ -219,7 +232,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16 inputs, fp32 accumulate", "data": "synthetic",
         "config": {"workload": "%s: %d q heads / %d kv heads, d=128, N=%d cached tokens, chunk %d, top-k %d+%d chunks, tree %d nodes, %d layer caches, batch 1" % (
             cfg.name, hq, hkv, n, cfg.chunk, cfg.k, cfg.n_sink, t, n_layers), "config_index": args.config,
-            "layers": n_layers, "n_tokens": n},
+            "layers": n_layers, "n_tokens": n, "launch": "hip graph replay" if args.graph else "eager"},
         "breakdown_us_per_layer": {k: round(v, 3) for k, v in parts.items()},
         "verify_plus_partial_us_per_layer": round(parts["verify"] + parts["partial"], 3),
         "cache_maintenance_us_per_layer": {k: round(v, 3) for k, v in maint.items()},

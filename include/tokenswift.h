@@ -65,6 +65,12 @@ typedef struct {
 
 enum { TS_OP_PARTIAL_ATTN = 1, TS_OP_TREE_VERIFY = 2 };
 
+/*
+ * All calls enqueue kernels on the caller's stream and return; none allocates, synchronises or
+ * copies, so a sequence of them can be captured in a HIP graph.  The first call of some shapes sets
+ * a kernel attribute (dynamic LDS above 64 KiB): run each shape once before capturing it.
+ */
+
 /* Text for a ts_status (static storage, never NULL). */
 const char *ts_strerror(int status);
 
