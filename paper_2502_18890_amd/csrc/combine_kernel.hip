@@ -3,7 +3,8 @@
 // its own keys.  Softmax attention over the union of the key sets is
 //   m* = max m_i,  l* = sum l_i 2^(m_i - m*),  out = sum O_i 2^(m_i - m*) / l*,
 // and the natural-log sum of exponentials is (m* + log2 l*) ln 2.
-// One wavefront per row, two output columns per lane.
+// One wavefront per row, two output columns per lane; the weights are computed once, one partial
+// per lane, and broadcast as the partials stream in, eight loads in flight.
 #include "ts_device.hpp"
 #include "ts_internal.hpp"
 
@@ -22,37 +23,37 @@ __global__ void __launch_bounds__(256) combine_kernel(const CombineParams p)
     const int64_t pitch = p.row_pitch;
     const int64_t first = (int64_t)h * p.n_part * pitch + row;   // partial pp at first + pp*pitch
 
+    // Lane pp holds the weight of partials pp, pp+64, ...: w = 2^(m_pp - m*), and l* = sum w l.
     float mstar = kNegBig;
     for (int pp = lane; pp < p.n_part; pp += 64)
         mstar = fmaxf(mstar, p.ws_ml[(first + (int64_t)pp * pitch) * 2]);
     mstar = wave_max(mstar);
 
     f32x2 acc = {0.f, 0.f};
-    float lstar = 0.f;
-    int pp = 0;
-    for (; pp + 4 <= p.n_part; pp += 4) {   // four partials in flight
-        f32x2 ml[4], o[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int64_t at = first + (int64_t)(pp + u) * pitch;
-            ml[u] = *reinterpret_cast<const f32x2 *>(p.ws_ml + at * 2);
-            o[u] = *reinterpret_cast<const f32x2 *>(p.ws_o + at * kHeadDim + lane * 2);
+    float lsum = 0.f;
+    for (int base = 0; base < p.n_part; base += 64) {
+        float w = 0.f;
+        if (base + lane < p.n_part) {
+            const f32x2 ml = *reinterpret_cast<const f32x2 *>(p.ws_ml + (first + (int64_t)(base + lane) * pitch) * 2);
+            w = fast_exp2(ml[0] - mstar);
+            lsum = fmaf(w, ml[1], lsum);
         }
+        const int n_here = p.n_part - base < 64 ? p.n_part - base : 64;
+        int u0 = 0;
+        for (; u0 + 8 <= n_here; u0 += 8) {   // eight partials in flight
+            f32x2 o[8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float w = fast_exp2(ml[u][0] - mstar);
-            lstar += w * ml[u][1];
-            acc += o[u] * w;
+            for (int u = 0; u < 8; ++u)
+                o[u] = *reinterpret_cast<const f32x2 *>(p.ws_o + (first + (int64_t)(base + u0 + u) * pitch) * kHeadDim + lane * 2);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += o[u] * __shfl(w, u0 + u, 64);
+        }
+        for (; u0 < n_here; ++u0) {
+            const f32x2 o = *reinterpret_cast<const f32x2 *>(p.ws_o + (first + (int64_t)(base + u0) * pitch) * kHeadDim + lane * 2);
+            acc += o * __shfl(w, u0, 64);
         }
     }
-    for (; pp < p.n_part; ++pp) {
-        const int64_t at = first + (int64_t)pp * pitch;
-        const f32x2 ml = *reinterpret_cast<const f32x2 *>(p.ws_ml + at * 2);
-        const float w = fast_exp2(ml[0] - mstar);
-        const f32x2 o = *reinterpret_cast<const f32x2 *>(p.ws_o + at * kHeadDim + lane * 2);
-        lstar += w * ml[1];
-        acc += o * w;
-    }
+    const float lstar = wave_sum(lsum);
     const int node = row / p.group, jj = row % p.group;
     const int64_t orow = (int64_t)node * p.n_q_heads + h * p.group + jj;
     const float inv = 1.0f / lstar;
