@@ -235,7 +235,7 @@ int ts_chunk_scores_from_sums(const float *ksum, int64_t ksum_stride_head, int n
  * Penalized probabilities and sampling pools (Sec. 3.4 "Contextual Penalty", Eq. 3; App. D).
  * ------------------------------------------------------------------------------------- */
 
-enum { TS_SAMPLE_FULL = 0, TS_SAMPLE_MIN_P = 1, TS_SAMPLE_TOP_P = 2 };
+enum { TS_SAMPLE_FULL = 0, TS_SAMPLE_MIN_P = 1, TS_SAMPLE_TOP_P = 2, TS_SAMPLE_ETA = 3 };
 
 /* Bytes of device workspace ts_penalized_probs needs (0 on invalid arguments). */
 size_t ts_sampling_workspace_bytes(int n_rows, int64_t vocab);
@@ -258,14 +258,16 @@ int ts_penalized_probs(const float *logits, int n_rows, int64_t vocab, const int
  * The pool is {i : probs[r][i] >= tau_r}: TS_SAMPLE_FULL: every token; TS_SAMPLE_MIN_P: tau = param *
  * max_i probs[r][i] (param = p_base in (0, 1]); TS_SAMPLE_TOP_P: the largest tau whose pool still holds
  * mass >= param (param = p in (0, 1]): the most probable tokens whose mass reaches p, tokens tied
- * with the last one all kept.  The draw inverts the pool's cumulative distribution, taken in order
+ * with the last one all kept; TS_SAMPLE_ETA: tau = min(param, param2 * exp(-h_r)) with h_r the entropy
+ * (natural log) of row r (param = epsilon in (0, 1], param2 = alpha > 0).  param2 is ignored by the
+ * other methods.  The draw inverts the pool's cumulative distribution, taken in order
  * of token id, at u[r]: the first pool token whose cumulative pool mass exceeds u[r] * pool mass.
  *   probs  fp32 [n_rows][vocab]; u  device fp32 [n_rows] in [0, 1) (clamped); tokens  int32 [n_rows]
  *   pool_threshold, pool_mass  fp32 [n_rows], nullable: tau_r and the pool's mass
  */
 int ts_sample_tokens(const float *probs, int n_rows, int64_t vocab, int method, float param,
-                     const float *u, int32_t *tokens, float *pool_threshold, float *pool_mass,
-                     void *stream);
+                     float param2, const float *u, int32_t *tokens, float *pool_threshold,
+                     float *pool_mass, void *stream);
 
 /*
  * Tuning hook (not needed for correct results): overrides a launch-geometry choice until

@@ -3,8 +3,9 @@
 Plain numpy in float64; shares nothing with the GPU library.  Passages followed:
   penalized_probs   Sec. 3.4 "Contextual Penalty", Eq. 3: softmax of l_i / (t * I_i) with I_i = theta for
                     tokens that occur among the W most recent generated tokens and 1 otherwise.
-  pool_threshold    App. D: the sampling pools of min-p (probability >= p_base * p_max) and top-p (the
-                    most probable tokens whose mass reaches p), both written as "probability >= tau".
+  pool_threshold    App. D: the sampling pools of min-p (probability >= p_base * p_max), top-p (the most
+                    probable tokens whose mass reaches p) and eta-sampling (probability >= min(epsilon,
+                    alpha * exp(-entropy))), all written as "probability >= tau".
   sample            App. D: the next token is drawn from the pool with the renormalised probabilities;
                     here by inverting the pool's cumulative distribution, taken in order of token id,
                     at a uniform number that is passed in.
@@ -12,7 +13,7 @@ Pins: tests/test_sampling_pins.py.
 """
 import numpy as np
 
-FULL, MIN_P, TOP_P = 0, 1, 2
+FULL, MIN_P, TOP_P, ETA = 0, 1, 2, 3
 
 
 def penalized_probs(logits, window, temperature, theta):
@@ -27,7 +28,7 @@ def penalized_probs(logits, window, temperature, theta):
     return e / e.sum(axis=1, keepdims=True)
 
 
-def pool_threshold(p_row, method, param):
+def pool_threshold(p_row, method, param, param2=0.0):
     """Probability threshold tau of the pool {v : p[v] >= tau} for one row.
 
     The product p_base * p_max and the comparison are taken in float32 when the row is float32
@@ -49,14 +50,19 @@ def pool_threshold(p_row, method, param):
                 tau = p[v]
                 break
         return tau
+    if method == ETA:
+        # eta = min(epsilon, alpha * exp(-h)), h = entropy of the row (natural log); param = epsilon, param2 = alpha
+        q = p.astype(np.float64)
+        h = -float(np.sum(np.where(q > 0, q * np.log(np.where(q > 0, q, 1.0)), 0.0)))
+        return p.dtype.type(min(float(param), float(param2) * np.exp(-h)))
     raise ValueError(method)
 
 
-def sample(p_row, method, param, u):
+def sample(p_row, method, param, u, param2=0.0):
     """-> (token, pool_mass, margin): margin = distance of u*pool_mass to the nearest step of the
     pool's cumulative distribution, relative to pool_mass (how decisive the draw was)."""
     p = np.asarray(p_row)
-    tau = pool_threshold(p, method, param)
+    tau = pool_threshold(p, method, param, param2)
     in_pool = p >= tau
     w = np.where(in_pool, p.astype(np.float64), 0.0)
     cdf = np.cumsum(w)

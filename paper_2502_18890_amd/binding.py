@@ -72,7 +72,7 @@ def load_library():
     lib.ts_sampling_workspace_bytes.argtypes = [ci, i64]
     lib.ts_sampling_workspace_bytes.restype = ctypes.c_size_t
     lib.ts_penalized_probs.argtypes = [vp, ci, i64, vp, ci, cf, cf, vp, vp, ctypes.c_size_t, vp]
-    lib.ts_sample_tokens.argtypes = [vp, ci, i64, ci, cf, vp, vp, vp, vp, vp]
+    lib.ts_sample_tokens.argtypes = [vp, ci, i64, ci, cf, cf, vp, vp, vp, vp, vp]
     lib.ts_penalized_probs.restype = ci
     lib.ts_sample_tokens.restype = ci
     for name in ("ts_tune_set", "ts_chunk_scores", "ts_topk_chunks", "ts_partial_kv_attn",
@@ -282,7 +282,7 @@ def chunk_scores_from_sums(ksum: torch.Tensor, n_tokens: int, q: torch.Tensor, c
 
 
 # ---- penalized probabilities and sampling ------------------------------------------------------------
-SAMPLE_FULL, SAMPLE_MIN_P, SAMPLE_TOP_P = 0, 1, 2
+SAMPLE_FULL, SAMPLE_MIN_P, SAMPLE_TOP_P, SAMPLE_ETA = 0, 1, 2, 3
 
 
 def penalized_probs(logits: torch.Tensor, window: Optional[torch.Tensor], temperature: float, theta: float,
@@ -305,7 +305,8 @@ def penalized_probs(logits: torch.Tensor, window: Optional[torch.Tensor], temper
     return out
 
 
-def sample_tokens(probs: torch.Tensor, method: int, param: float, u: torch.Tensor, want_pool: bool = False):
+def sample_tokens(probs: torch.Tensor, method: int, param: float, u: torch.Tensor, want_pool: bool = False,
+                  param2: float = 0.0):
     """probs fp32 [R,V], u fp32 [R] -> tokens int32 [R] (and (threshold, mass) fp32 [R] each)."""
     lib = load_library()
     if probs.dtype != torch.float32 or probs.dim() != 2 or not probs.is_contiguous():
@@ -315,7 +316,7 @@ def sample_tokens(probs: torch.Tensor, method: int, param: float, u: torch.Tenso
     tokens = torch.empty(r, dtype=torch.int32, device=probs.device)
     thr = torch.empty(r, dtype=torch.float32, device=probs.device) if want_pool else None
     mass = torch.empty(r, dtype=torch.float32, device=probs.device) if want_pool else None
-    _check(lib.ts_sample_tokens(probs.data_ptr(), r, v, int(method), float(param), u.data_ptr(), tokens.data_ptr(),
+    _check(lib.ts_sample_tokens(probs.data_ptr(), r, v, int(method), float(param), float(param2), u.data_ptr(), tokens.data_ptr(),
                                 thr.data_ptr() if want_pool else None, mass.data_ptr() if want_pool else None, _stream()),
            "ts_sample_tokens")
     return (tokens, thr, mass) if want_pool else tokens

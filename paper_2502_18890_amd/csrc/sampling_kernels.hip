@@ -1,5 +1,5 @@
 // Penalized probabilities and pool sampling of TokenSwift (Sec. 3.4 "Contextual Penalty", Eq. 3;
-// App. D: min-p and top-p pools), for gfx950.  Rows are vocabulary-sized (32K..152K fp32): the
+// App. D: min-p, top-p and eta pools), for gfx950.  Rows are vocabulary-sized (32K..152K fp32): the
 // probabilities pass is a split softmax bound by HBM (read the logits twice, write the
 // probabilities once); the sampler works on one row per workgroup out of L2.
 //
@@ -209,6 +209,15 @@ __global__ void __launch_bounds__(1024) sample_kernel(const SampleParams p)
         for (int i = 0; i < 16; ++i) p_max = fmaxf(p_max, red[i]);
         if (p.method == kSampleMinP) {
             tau = p.param * p_max;
+        } else if (p.method == kSampleEta) {
+            // eta = min(epsilon, alpha * exp(-h)), h = -sum p ln p
+            float hs = 0.f;
+            w.for_each_chunk([&](int64_t, int64_t, const float (&v)[4]) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) hs += (v[e] > 0.f) ? v[e] * fast_log2(v[e]) : 0.f;
+            });
+            const float h = -kLn2 * block_sum16(wave_sum(hs), red, wave, lane);
+            tau = fminf(p.param, p.param2 * fast_exp2(-h * kLog2e));
         } else {
             // top-p: the largest threshold whose pool still holds mass >= param, by bisection on the
             // bit pattern (probabilities are non-negative floats, so their bits order like their values)

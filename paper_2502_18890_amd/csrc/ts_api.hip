@@ -526,13 +526,14 @@ int ts_penalized_probs(const float *logits, int n_rows, int64_t vocab, const int
 }
 
 int ts_sample_tokens(const float *probs, int n_rows, int64_t vocab, int method, float param,
-                     const float *u, int32_t *tokens, float *pool_threshold, float *pool_mass,
-                     void *stream)
+                     float param2, const float *u, int32_t *tokens, float *pool_threshold,
+                     float *pool_mass, void *stream)
 {
     if (!probs || !u || !tokens) return TS_ERR_NULL;
     if (n_rows < 1 || vocab < 1) return TS_ERR_SHAPE;
     if (vocab > (1 << 24)) return TS_ERR_UNSUPPORTED;
-    if (method != TS_SAMPLE_FULL && method != TS_SAMPLE_MIN_P && method != TS_SAMPLE_TOP_P) return TS_ERR_UNSUPPORTED;
+    if (method < TS_SAMPLE_FULL || method > TS_SAMPLE_ETA) return TS_ERR_UNSUPPORTED;
+    if (method == TS_SAMPLE_ETA && !(param2 > 0.f && param2 < 3.0e38f)) return TS_ERR_UNSUPPORTED;
     if (method != TS_SAMPLE_FULL && !(param > 0.f && param <= 1.f)) return TS_ERR_UNSUPPORTED;
     ts::SampleParams p;
     p.probs = probs;
@@ -544,6 +545,7 @@ int ts_sample_tokens(const float *probs, int n_rows, int64_t vocab, int method, 
     p.n_rows = n_rows;
     p.method = method;
     p.param = param;
+    p.param2 = param2;
     return ts::launch_sample(p, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 

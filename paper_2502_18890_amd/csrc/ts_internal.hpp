@@ -161,7 +161,7 @@ struct PenaltyParams {
 int sampling_slices(int64_t vocab);
 hipError_t launch_penalized_probs(const PenaltyParams &p, hipStream_t stream);
 
-enum { kSampleFull = 0, kSampleMinP = 1, kSampleTopP = 2 };
+enum { kSampleFull = 0, kSampleMinP = 1, kSampleTopP = 2, kSampleEta = 3 };
 struct SampleParams {
     const float *probs;       // fp32 [n_rows][vocab]
     const float *u;           // fp32 [n_rows], uniform in [0, 1)
@@ -170,7 +170,7 @@ struct SampleParams {
     float *pool_mass;         // [n_rows] or nullptr
     int64_t vocab;
     int n_rows, method;
-    float param;
+    float param, param2;
 };
 hipError_t launch_sample(const SampleParams &p, hipStream_t stream);
 

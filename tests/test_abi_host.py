@@ -198,8 +198,9 @@ def test_sampling_calls_reject_bad_arguments(lib):
     assert pp(v=(1 << 24) + 1) == TS_ERR_UNSUPPORTED
     assert pp(lg=0x1004) == TS_ERR_ALIGN
     assert pp(ws=None) == TS_ERR_WORKSPACE and pp(wb=16) == TS_ERR_WORKSPACE and pp(ws=0x10010) == TS_ERR_WORKSPACE
-    st = lambda pr=0x1000, r=4, v=1000, m=1, par=0.1, u=0x3000, tok=0x4000: lib.ts_sample_tokens(pr, r, v, m, par, u, tok, None, None, None)
+    st = lambda pr=0x1000, r=4, v=1000, m=1, par=0.1, u=0x3000, tok=0x4000, par2=0.0: lib.ts_sample_tokens(pr, r, v, m, par, par2, u, tok, None, None, None)
     assert st(pr=None) == TS_ERR_NULL and st(u=None) == TS_ERR_NULL and st(tok=None) == TS_ERR_NULL
     assert st(r=0) == TS_ERR_SHAPE and st(v=0) == TS_ERR_SHAPE
-    assert st(m=3) == TS_ERR_UNSUPPORTED and st(m=-1) == TS_ERR_UNSUPPORTED
+    assert st(m=4) == TS_ERR_UNSUPPORTED and st(m=-1) == TS_ERR_UNSUPPORTED
+    assert st(m=3, par=0.01, par2=0.0) == TS_ERR_UNSUPPORTED and st(m=3, par=0.0, par2=0.5) == TS_ERR_UNSUPPORTED
     assert st(par=0.0) == TS_ERR_UNSUPPORTED and st(par=1.5) == TS_ERR_UNSUPPORTED and st(m=2, par=float("nan")) == TS_ERR_UNSUPPORTED

@@ -54,14 +54,18 @@ def test_penalized_probs_peaked_and_flat_rows(ts):
     assert_close(got, O.penalized_probs(lg, window, 1.0, 1.2), "penalized probs, peaked/flat")
 
 
-def _check_draws(ts, probs_gpu, method, param, u):
+def _check_draws(ts, probs_gpu, method, param, u, param2=0.0):
     import torch
     p = probs_gpu.cpu().numpy()
-    tok, thr, mass = ts.sample_tokens(probs_gpu, method, param, torch.from_numpy(u).cuda(), want_pool=True)
+    tok, thr, mass = ts.sample_tokens(probs_gpu, method, param, torch.from_numpy(u).cuda(), want_pool=True, param2=param2)
     tok, thr, mass = tok.cpu().numpy(), thr.cpu().numpy(), mass.cpu().numpy()
     n_ambiguous = 0
     for r in range(p.shape[0]):
-        tau = O.pool_threshold(p[r], method, param)
+        tau = O.pool_threshold(p[r], method, param, param2)
+        if method == O.ETA:
+            # eta comes out of an fp32 entropy sum: equal to the oracle's to rounding, not bit for bit
+            assert abs(float(thr[r]) - float(tau)) <= 2e-5 * float(tau), (r, thr[r], tau)
+            tau = thr[r]
         if method == O.TOP_P:
             # the cut itself is a floating-point decision: accept the neighbouring thresholds when the mass
             # at the cut is within 1e-5 of param
@@ -94,6 +98,16 @@ def test_sampling_pools_and_draws(ts, method, param, r, v):
     u[0] = 0.0
     u[-1] = 0.99999
     _check_draws(ts, probs, method, param, u)
+
+
+@pytest.mark.parametrize("eps,alpha", [(0.0009, 0.03), (0.3, 0.5), (1.0, 5.0)])
+@pytest.mark.parametrize("r,v", [(24, 1000), (6, 128256)])
+def test_eta_sampling(ts, eps, alpha, r, v):
+    import torch
+    rng = np.random.default_rng(43)
+    lg = _logits(rng, r, v, spread=2.0)
+    probs = ts.penalized_probs(torch.from_numpy(lg).cuda(), None, 1.0, 1.0)
+    _check_draws(ts, probs, O.ETA, eps, rng.random(r).astype(np.float32), param2=alpha)
 
 
 def test_sampling_with_ties_and_tiny_vocab(ts):

@@ -68,6 +68,26 @@ def test_top_p_pool_is_the_smallest_prefix_of_the_sorted_tokens():
         assert q[q < tau].max(initial=0.0) <= pool.min()
 
 
+def test_eta_pool_closed_forms():
+    # uniform row over n tokens: entropy = log n, so alpha * exp(-h) = alpha / n
+    n = 50
+    p = np.full(n, 1.0 / n)
+    assert np.isclose(O.pool_threshold(p, O.ETA, 0.5, 2.0), 2.0 / n)          # alpha/n < epsilon
+    assert np.isclose(O.pool_threshold(p, O.ETA, 0.001, 2.0), 0.001)         # epsilon caps it
+    # one-hot row: entropy 0, eta = min(epsilon, alpha); pool = the hot token when eta <= 1
+    hot = np.zeros(10); hot[3] = 1.0
+    tau = O.pool_threshold(hot, O.ETA, 0.9, 0.5)
+    assert np.isclose(tau, 0.5) and {v for v in range(10) if hot[v] >= tau} == {3}
+    # two tokens (a, 1-a): entropy by the textbook formula
+    a = 0.2
+    h = -(a * np.log(a) + (1 - a) * np.log(1 - a))
+    assert np.isclose(O.pool_threshold(np.array([a, 1 - a]), O.ETA, 1.0, 0.3), 0.3 * np.exp(-h))
+    from scipy.stats import entropy
+    rng = np.random.default_rng(7)
+    q = softmax(rng.standard_normal(300) * 2)
+    assert np.isclose(O.pool_threshold(q, O.ETA, 1.0, 0.7), 0.7 * np.exp(-entropy(q)))
+
+
 def test_ties_at_the_cut_are_kept_together():
     p = np.array([0.3, 0.2, 0.2, 0.2, 0.1])
     tau = O.pool_threshold(p, O.TOP_P, 0.45)               # 0.3 + one of the 0.2s reaches 0.45: all three 0.2s stay
