@@ -272,7 +272,7 @@ int ts_sample_tokens(const float *probs, int n_rows, int64_t vocab, int method, 
 /*
  * Tuning hook (not needed for correct results): overrides a launch-geometry choice until
  * reset with value 0.  Names: "verify_splits" (number of cache splits per KV head);
- * "verify_variant" (1..4: alternative kernel shapes of the verification pass);
+ * "verify_variant" (1..3: alternative kernel shapes of the verification pass);
  * "verify_stage" (1: ts_tree_verify_attn enqueues only its split kernel, 2: only its merge
  * kernel -- for timing one kernel alone; outputs are then not meaningful).  Returns TS_OK, or
  * TS_ERR_UNSUPPORTED for an unknown name or a value the kernels cannot run.  The same

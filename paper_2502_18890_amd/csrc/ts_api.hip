@@ -106,7 +106,7 @@ bool partial_chunk_ok(int chunk_size) { return chunk_size >= 16 && chunk_size <=
 // Kernel shape by number of query rows per KV head.  Up to 32 rows the pass is purely HBM-bound
 // and the 16x16x32 kernel with its small workgroups (many of them per CU) is used; beyond that
 // the 32x32x16 kernel, in row tiles of at most 384 rows.  Defaults are the fastest measured
-// shapes; variant 1..4 select the alternatives (all produce the same results).
+// shapes; variant 1..3 select the alternatives (all produce the same results).
 bool ts::verify_shape(int n_rows, int variant, VerifyShape *out)
 {
     if (n_rows < 1 || n_rows > TS_MAX_GROUP * TS_MAX_TREE) return false;
@@ -125,7 +125,6 @@ bool ts::verify_shape(int n_rows, int variant, VerifyShape *out)
     else if (r <= 128) {
         if (variant == 2) *out = VerifyShape{kWide_1x4, 128, 2};
         else if (variant == 3) *out = VerifyShape{kWide_1x4k2, 128, 1};
-        else if (variant == 4) *out = VerifyShape{kWide_1x4p, 128, 1};
         else *out = VerifyShape{kWide_1x4k3, 128, 1};
     } else if (r <= 256) *out = VerifyShape{variant == 2 ? kWide_2x4 : kWide_1x8, 256, 1};
     else {
@@ -164,7 +163,7 @@ int ts_tune_set(const char *name, int value)
         return TS_OK;
     }
     if (strcmp(name, "verify_variant") == 0) {
-        if (value > 4) return TS_ERR_UNSUPPORTED;
+        if (value > 3) return TS_ERR_UNSUPPORTED;
         g_tune.verify_variant = value;
         return TS_OK;
     }

@@ -37,7 +37,6 @@ enum VerifyKernelId {
     kWide_1x1b,       // deeper ring, two workgroups per CU
     kWide_1x2,
     kWide_1x4,
-    kWide_1x4p,       // software-pipelined main loop
     kWide_1x4k2,      // two key groups, query fragments in LDS
     kWide_1x4k3,      // three key groups, query fragments in LDS
     kWide_2x4,

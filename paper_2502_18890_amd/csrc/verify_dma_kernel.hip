@@ -136,16 +136,20 @@ verify_dma_kernel(const VerifyParams p)
         const int f = (ii >= 8) ? (((R >> 2) & 1) << 3) : (R & 15);
         goff[i] = (uint32_t)(R * tstride * 2 + ((j ^ f) << 4));
     }
-    auto issue_tile = [&](int64_t tile) {
-        const int64_t t0 = t_begin + tile * kTileKeys;
-        const int64_t span = t0 < t_end ? (t_end - t0 - 1) * tstride * 2 + 256 : 0;   // bytes up to the end of the last valid row
-        const uint32_t nrec = span > 0xffffffffLL ? 0xffffffffu : (uint32_t)span;
-        const int64_t tb = t0 < t_end ? t0 : t_begin;            // keep the base inside the allocation
-        const __amdgpu_buffer_rsrc_t rk =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(kbase + tb * tstride), 0, nrec, 0x00020000);
-        const __amdgpu_buffer_rsrc_t rv =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(vbase + tb * tstride), 0, nrec, 0x00020000);
-        unsigned char *stage = lds + (int)(tile % NS) * kStageBytes;
+    // Tiles are issued and consumed strictly in order, so both sides keep running cursors (a few
+    // scalar additions per tile) instead of recomputing addresses from the tile number.
+    constexpr uint32_t kRingBytes = NS * kStageBytes;
+    const int64_t tile_elems = (int64_t)kTileKeys * tstride;     // elements between consecutive tiles
+    const uint16_t *kfill = kbase + t_begin * tstride;
+    const uint16_t *vfill = vbase + t_begin * tstride;
+    // bytes from the first row of the next tile to fill up to the end of the last valid row (<= 0: none)
+    int64_t fill_rem = (t_end - t_begin - 1) * tstride * 2 + 256;
+    uint32_t fill_stage = 0;
+    auto issue_tile = [&]() {
+        const uint32_t nrec = fill_rem <= 0 ? 0u : (fill_rem > 0xffffffffLL ? 0xffffffffu : (uint32_t)fill_rem);
+        const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(kfill), 0, nrec, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(vfill), 0, nrec, 0x00020000);
+        unsigned char *stage = lds + fill_stage;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int ii = wave * LPW + i;                       // wave-uniform
@@ -155,6 +159,11 @@ verify_dma_kernel(const VerifyParams p)
             else
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void_ptr)(stage + kVHalf + (ii - 8) * 1024), 16, go, 0, 0, 0);
         }
+        kfill += tile_elems;     // past the range the descriptor covers 0 bytes, so the base is never dereferenced
+        vfill += tile_elems;
+        fill_rem -= tile_elems * 2;
+        fill_stage += kStageBytes;
+        if (fill_stage >= kRingBytes) fill_stage = 0;
     };
 
     // per-lane LDS read offsets inside a stage
@@ -166,9 +175,9 @@ verify_dma_kernel(const VerifyParams p)
     for (int dg = 0; dg < 2; ++dg)
         voffl[dg] = kVHalf + quad * 1024 + ((((dg << 3) | (j >> 1)) ^ ((quad & 1) << 3)) << 4) + ((j & 1) << 3);
 
-    const int64_t n_tiles = (t_end - t_begin + kTileKeys - 1) / kTileKeys;
+    const int n_tiles = (int)((t_end - t_begin + kTileKeys - 1) / kTileKeys);
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s) issue_tile(s);   // tiles past the range load nothing but still count
+    for (int s = 0; s < NS - 1; ++s) issue_tile();   // tiles past the range load nothing but still count
 
     // Now wait for the query and mask loads (older than every tile load, so the tile loads stay
     // in flight) -- here, not at their first use inside the main loop, where the wait would be
@@ -316,17 +325,22 @@ verify_dma_kernel(const VerifyParams p)
     };
 
     // full tiles first, then (cache ranges) at most one ragged tile; the tree split is all ragged
-    auto step = [&](auto ragged_tag, int64_t it) {
-        wait_vmcnt<(NS - 2) * LPW>();                 // this wavefront's pieces of tile `it` have landed
-        // ... and everyone's; all are done with tile it-1.  A bare s_barrier: __syncthreads() would add a
+    uint32_t use_stage = 0;          // stage of the tile being consumed
+    int64_t t0_cur = t_begin;        // its first token
+    auto step = [&](auto ragged_tag) {
+        wait_vmcnt<(NS - 2) * LPW>();                 // this wavefront's pieces of the next tile have landed
+        // ... and everyone's; all are done with the previous tile.  A bare s_barrier: __syncthreads() would add a
         // fence that waits for every outstanding load, i.e. for the whole prefetched ring.
         if (WR > 1) asm volatile("s_barrier" ::: "memory");
-        issue_tile(it + NS - 1);                      // refill the stage that tile it-1 occupied
-        process_tile(ragged_tag, lds + (int)(it % NS) * kStageBytes, t_begin + it * kTileKeys);
+        issue_tile();                                 // refill the stage that the previous tile occupied
+        process_tile(ragged_tag, lds + use_stage, t0_cur);
+        use_stage += kStageBytes;
+        if (use_stage >= kRingBytes) use_stage = 0;
+        t0_cur += kTileKeys;
     };
-    const int64_t n_full = is_tree ? 0 : (t_end - t_begin) / kTileKeys;
-    for (int64_t it = 0; it < n_full; ++it) step(std::false_type{}, it);
-    for (int64_t it = n_full; it < n_tiles; ++it) step(std::true_type{}, it);
+    const int n_full = is_tree ? 0 : (int)((t_end - t_begin) / kTileKeys);
+    for (int it = 0; it < n_full; ++it) step(std::false_type{});
+    for (int it = n_full; it < n_tiles; ++it) step(std::true_type{});
     wait_vmcnt<0>();   // drain the loads issued past the range before the workgroup's LDS is released
 
     // ---- write the partial: (m, l) and unnormalised O for every live row ----------------------

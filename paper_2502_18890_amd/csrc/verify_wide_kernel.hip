@@ -80,16 +80,16 @@ __device__ __forceinline__ float swap32_sum(float x)
 constexpr int loads_per_wave(int wr) { return wr >= 16 ? 1 : (wr >= 8 ? 2 : (wr >= 4 ? 4 : (wr >= 2 ? 8 : 16))); }
 
 // NRB: 32-row blocks per wavefront; WR: wavefronts per key group (along the query rows); KG: key
-// groups; NS: LDS stages per key group (one or two tiles resident, the others in flight); OCC:
+// groups; NS: LDS stages per key group (one tile resident, the others in flight); OCC:
 // wavefronts per SIMD the register budget is cut for; QLDS: query fragments live in LDS instead
-// of registers; PIPE: S^T of the next tile is issued before the softmax of the current one.
-template <int NRB, int WR, int KG, int NS, int OCC, bool QLDS, bool PIPE>
+// of registers.
+template <int NRB, int WR, int KG, int NS, int OCC, bool QLDS>
 __global__ void __launch_bounds__(64 * WR * KG) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 verify_wide_kernel(const VerifyParams p)
 {
     constexpr int NT = 64 * WR * KG;
     constexpr int LPW = loads_per_wave(WR);   // load instructions per loading wavefront per tile (16 x 1 KiB = one tile)
-    constexpr int RES = PIPE ? 2 : 1;   // tiles resident in LDS while the others are in flight
+    constexpr int RES = 1;                    // tiles resident in LDS while the others are in flight
     static_assert(NS >= RES + 1, "bad shape");
     static_assert((NS - RES - 1) * LPW <= 63, "too many loads in flight for vmcnt");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -184,26 +184,37 @@ verify_wide_kernel(const VerifyParams p)
         const int f = (ii >= 8) ? ((R & 3) << 2) : (R & 15);
         goff[i] = (uint32_t)(R * tstride * 2 + ((j ^ f) << 4));
     }
-    auto stage_of = [&](int64_t u) { return lds + ((int)(u % NS) * KG + kg) * kStageBytes; };
-    auto issue_tile = [&](int64_t u) {
-        if (!loader) return;
-        const int64_t t0 = t_begin + (u * KG + kg) * kTileKeys;
-        const int64_t span = t0 < t_end ? (t_end - t0 - 1) * tstride * 2 + 256 : 0;   // bytes up to the end of the last valid row
-        const uint32_t nrec = span > 0xffffffffLL ? 0xffffffffu : (uint32_t)span;
-        const int64_t tb = t0 < t_end ? t0 : t_begin;            // keep the base inside the allocation
-        const __amdgpu_buffer_rsrc_t rk =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(kbase + tb * tstride), 0, nrec, 0x00020000);
-        const __amdgpu_buffer_rsrc_t rv =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(vbase + tb * tstride), 0, nrec, 0x00020000);
-        unsigned char *stage = stage_of(u);
+    // Tiles are issued and consumed strictly in order, so both sides keep running cursors (a few
+    // scalar additions per step) instead of recomputing addresses from the tile number: the scalar
+    // unit is shared by the whole CU and this code sits on every wavefront's path after the barrier.
+    constexpr uint32_t kRingBytes = NS * KG * kStageBytes;
+    const uint32_t stage0 = kg * kStageBytes;
+    const int64_t tile_elems = (int64_t)KG * kTileKeys * tstride;      // elements between consecutive group tiles
+    const uint16_t *kfill = kbase + (t_begin + (int64_t)kg * kTileKeys) * tstride;
+    const uint16_t *vfill = vbase + (t_begin + (int64_t)kg * kTileKeys) * tstride;
+    // bytes from the first row of the next tile to fill up to the end of the last valid row (<= 0: none)
+    int64_t fill_rem = (t_end - (t_begin + (int64_t)kg * kTileKeys) - 1) * tstride * 2 + 256;
+    uint32_t fill_stage = stage0;
+    auto issue_tile = [&]() {
+        if (loader) {
+            const uint32_t nrec = fill_rem <= 0 ? 0u : (fill_rem > 0xffffffffLL ? 0xffffffffu : (uint32_t)fill_rem);
+            const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(kfill), 0, nrec, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(vfill), 0, nrec, 0x00020000);
+            unsigned char *stage = lds + fill_stage;
 #pragma unroll
-        for (int i = 0; i < LPW; ++i) {
-            const int ii = wave * LPW + i;                       // wave-uniform
-            const uint32_t go = goff[i];
-            if (ii < 8)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void_ptr)(stage + ii * 1024), 16, go, 0, 0, 0);
-            else
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void_ptr)(stage + kVHalf + (ii - 8) * 1024), 16, go, 0, 0, 0);
+            for (int i = 0; i < LPW; ++i) {
+                const int ii = wave * LPW + i;                       // wave-uniform
+                const uint32_t go = goff[i];
+                if (ii < 8)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void_ptr)(stage + ii * 1024), 16, go, 0, 0, 0);
+                else
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void_ptr)(stage + kVHalf + (ii - 8) * 1024), 16, go, 0, 0, 0);
+            }
+            kfill += tile_elems;     // past the range the descriptor covers 0 bytes, so the base is never dereferenced
+            vfill += tile_elems;
+            fill_rem -= tile_elems * 2;
+            fill_stage += KG * kStageBytes;
+            if (fill_stage >= kRingBytes) fill_stage = stage0;
         }
     };
 
@@ -222,9 +233,9 @@ verify_wide_kernel(const VerifyParams p)
     }
 
     const int64_t n_tiles = (t_end - t_begin + kTileKeys - 1) / kTileKeys;
-    const int64_t n_steps = (n_tiles + KG - 1) / KG;   // group tiles per key group (some groups may run one empty)
+    const int n_steps = (int)((n_tiles + KG - 1) / KG);   // group tiles per key group (some groups may run one empty)
 #pragma unroll
-    for (int s = 0; s < NS - RES; ++s) issue_tile(s);   // tiles past the range load nothing but still count
+    for (int s = 0; s < NS - RES; ++s) issue_tile();   // tiles past the range load nothing but still count
 
     // Now wait for the query and mask loads (older than every tile load, so the tile loads stay
     // in flight) -- here, not at their first use inside the main loop, where the wait would be
@@ -407,67 +418,39 @@ verify_wide_kernel(const VerifyParams p)
         }
     };
 
-    // Main loop over group tiles u = 0 .. n_steps-1 (tile u*KG + kg of the range).  Plain form: one
-    // group tile resident, NS-1 in flight.  Pipelined form: step u needs the keys of group tile u+1
-    // and the values of group tile u, so two are resident and NS-2 in flight.  Every wavefront of
-    // the workgroup runs the same number of steps (one barrier each), whichever instantiation of
-    // the body it takes.
-    const int64_t n_full_steps = is_tree ? 0 : ((t_end - t_begin) / kTileKeys) / KG;   // steps whose tiles are full for every key group
-    auto t0_of = [&](int64_t u) { return t_begin + (u * KG + kg) * kTileKeys; };
-    auto sync_and_refill = [&](int64_t landed) {
-        // this wavefront's pieces of group tile `landed` have landed: the NS-RES-1 issued after it
+    // Main loop over group tiles u = 0 .. n_steps-1 (tile u*KG + kg of the range): one group tile
+    // resident, NS-1 in flight.  Every wavefront of the workgroup runs the same number of steps
+    // (one barrier each), whichever instantiation of the body it takes.
+    const int n_full_steps = is_tree ? 0 : (int)(((t_end - t_begin) / kTileKeys) / KG);   // steps whose tiles are full for every key group
+    uint32_t use_stage = stage0;                                   // stage of the group tile being consumed
+    int64_t t0_cur = t_begin + (int64_t)kg * kTileKeys;            // its first token
+    auto sync_and_refill = [&]() {
+        // this wavefront's pieces of the next group tile have landed: the NS-RES-1 issued after it
         // may still be in flight
         wait_vmcnt<(NS - RES - 1) * LPW>();
-        // ... and everyone's; all are done with group tile landed-RES.  A bare s_barrier:
+        // ... and everyone's; all are done with the previous group tile.  A bare s_barrier:
         // __syncthreads() would add a fence that waits for every outstanding load, i.e. for the
         // whole prefetched ring.
         if (WR * KG > 1) asm volatile("s_barrier" ::: "memory");
-        issue_tile(landed + NS - RES);                // refills the stage that group tile landed-RES occupied
+        issue_tile();                                              // refills the stage the previous group tile occupied
     };
     auto run = [&](auto live_tag) {
         constexpr int L = decltype(live_tag)::value;
         f32x16 s_cur[L > 0 ? L : 1];
-        if (!PIPE) {
-            // full tiles first, then the ragged end; the tree split is all ragged
-            auto step = [&](auto ragged_tag, int64_t u) {
-                sync_and_refill(u);
-                if (L > 0) {
-                    qk_tile(live_tag, stage_of(u), s_cur);
-                    pv_tile(live_tag, ragged_tag, stage_of(u), t0_of(u), s_cur);
-                }
-            };
-            for (int64_t u = 0; u < n_full_steps; ++u) step(std::false_type{}, u);
-            for (int64_t u = n_full_steps; u < n_steps; ++u) step(std::true_type{}, u);
-            return;
-        }
-        // Pipelined: S^T of group tile u+1 is issued before the softmax of group tile u.  The
-        // steady state is unrolled twice so that the two logit buffers swap roles without copies.
-        f32x16 s_nxt[L > 0 ? L : 1];
-        sync_and_refill(0);   // prologue: group tile 0
-        if (L > 0) qk_tile(live_tag, stage_of(0), s_cur);
-        int64_t u = 0;
-        for (; u + 2 < n_full_steps; u += 2) {   // group tiles u, u+1 full; u+1, u+2 exist
-            sync_and_refill(u + 1);
+        // full tiles first, then the ragged end; the tree split is all ragged
+        auto step = [&](auto ragged_tag) {
+            sync_and_refill();
             if (L > 0) {
-                qk_tile(live_tag, stage_of(u + 1), s_nxt);
-                pv_tile(live_tag, std::false_type{}, stage_of(u), t0_of(u), s_cur);
+                const unsigned char *stage = lds + use_stage;
+                qk_tile(live_tag, stage, s_cur);
+                pv_tile(live_tag, ragged_tag, stage, t0_cur, s_cur);
             }
-            sync_and_refill(u + 2);
-            if (L > 0) {
-                qk_tile(live_tag, stage_of(u + 2), s_cur);
-                pv_tile(live_tag, std::false_type{}, stage_of(u + 1), t0_of(u + 1), s_nxt);
-            }
-        }
-        for (; u < n_steps; ++u) {               // the last few group tiles, ragged ones included
-            sync_and_refill(u + 1);
-            if (L > 0) {
-                if (u + 1 < n_steps) qk_tile(live_tag, stage_of(u + 1), s_nxt);
-                if (u < n_full_steps) pv_tile(live_tag, std::false_type{}, stage_of(u), t0_of(u), s_cur);
-                else pv_tile(live_tag, std::true_type{}, stage_of(u), t0_of(u), s_cur);
-#pragma unroll
-                for (int rb = 0; rb < L; ++rb) s_cur[rb] = s_nxt[rb];
-            }
-        }
+            use_stage += KG * kStageBytes;
+            if (use_stage >= kRingBytes) use_stage = stage0;
+            t0_cur += KG * kTileKeys;
+        };
+        for (int u = 0; u < n_full_steps; ++u) step(std::false_type{});
+        for (int u = n_full_steps; u < n_steps; ++u) step(std::true_type{});
     };
     if (nrb_live == NRB) run(std::integral_constant<int, NRB>{});
     else run(std::integral_constant<int, NRB - 1>{});   // round-robin dealing: never fewer than NRB-1 unless none at all
@@ -553,7 +536,7 @@ verify_wide_kernel(const VerifyParams p)
     }
 }
 
-template <int NRB, int WR, int KG, int NS, int OCC, bool QLDS, bool PIPE = false>
+template <int NRB, int WR, int KG, int NS, int OCC, bool QLDS>
 hipError_t launch_one(const VerifyParams &p, hipStream_t stream)
 {
     constexpr int kRows = 32 * NRB * WR;
@@ -563,13 +546,13 @@ hipError_t launch_one(const VerifyParams &p, hipStream_t stream)
     if (p.rows_per_wg > kRows || p.rows_per_wg % 32 != 0) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (lds_bytes > 64 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS, PIPE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(p.n_split + 1, p.n_kv_heads, (p.n_rows + p.rows_per_wg - 1) / p.rows_per_wg);
-    hipLaunchKernelGGL((verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS, PIPE>), grid, dim3(64 * WR * KG), lds_bytes, stream, p);
+    hipLaunchKernelGGL((verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS>), grid, dim3(64 * WR * KG), lds_bytes, stream, p);
     return hipGetLastError();
 }
 
@@ -582,7 +565,6 @@ hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t 
         case kWide_1x1b: return launch_one<1, 1, 1, 4, 2, false>(p, stream);
         case kWide_1x2: return launch_one<1, 2, 1, 4, 2, false>(p, stream);
         case kWide_1x4: return launch_one<1, 4, 1, 4, 2, false>(p, stream);
-        case kWide_1x4p: return launch_one<1, 4, 1, 8, 1, false, true>(p, stream);
         case kWide_1x4k2: return launch_one<1, 4, 2, 3, 2, true>(p, stream);
         case kWide_1x4k3: return launch_one<1, 4, 3, 2, 3, true>(p, stream);
         case kWide_2x4: return launch_one<2, 4, 1, 6, 1, false>(p, stream);

@@ -251,7 +251,7 @@ def test_verify_split_override_and_determinism(ts):
         ts.tune_set("verify_splits", 0)
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
 @pytest.mark.parametrize("hq,hkv,n,t", [(8, 2, 1000, 8), (32, 8, 2085, 32), (12, 2, 999, 16), (40, 8, 700, 64),
                                         (4, 4, 130, 3), (48, 8, 333, 64), (64, 8, 200, 64), (2, 2, 300, 32),
                                         (16, 2, 450, 25), (4, 4, 97, 128), (32, 8, 260, 100), (16, 2, 129, 128), (32, 8, 70, 32),
