@@ -3,8 +3,10 @@
 // 32 query rows per KV head (GQA groups, wide trees), built on v_mfma_f32_32x32x16_bf16.
 //
 // On this part the 32x32x16 instruction delivers twice the flops per issue slot of 16x16x32,
-// and once g*T reaches ~100 rows the pass is no longer purely HBM-bound: the matrix and vector
-// units have to be kept busy at the same time.  Work decomposition: one workgroup = one KV
+// and once g*T reaches ~100 rows the pass is no longer HBM-bound: matrix cores, vector units and
+// LDS are all busy and the chip lowers its clock (1.8 GHz measured under this kernel, 2.4 GHz
+// under the 32-row one), so what counts is work per key, not the order it is issued in.  Work
+// decomposition: one workgroup = one KV
 // head x one contiguous range of cached tokens (split index n_split = the tree tokens with the
 // ancestor mask) x up to 32*NRB*WR query rows; 32-row blocks are dealt round-robin to WR
 // wavefronts, every wavefront applies a 32-key tile to its own blocks.  A workgroup may hold KG
@@ -258,11 +260,9 @@ verify_wide_kernel(const VerifyParams p)
 
     // One 32-key tile against all of this wavefront's row blocks.  RAGGED tiles (the last one of
     // a range, every tile of the tree split) mask keys; full tiles carry no masking code.
-    // The tile body comes in two pieces so that the main loop can be software-pipelined: the
-    // matrix work S^T(tile t+1) is independent of the vector work softmax(tile t), and issuing it
-    // first lets one wavefront keep both units busy.  L = number of row blocks computed (compile
-    // time, so that the body is straight-line code the scheduler can interleave freely); a block
-    // beyond the wavefront's live ones holds zero queries and is never written back.
+    // L = number of row blocks computed (compile time, so that the body is straight-line code the
+    // scheduler can interleave freely); a block beyond the wavefront's live ones holds zero queries
+    // and is never written back.
 
     // ---- S^T = K . Q^T of one tile --------------------------------------------------------------
     auto qk_tile = [&](auto live_tag, const unsigned char *stage, auto &sacc) {
