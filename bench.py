@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--kernel-loops", type=int, default=2, help="extra sweeps of the verify kernel alone for the roofline figure")
     ap.add_argument("--graph", action="store_true",
                     help="capture one whole step (all layers) in a HIP graph and time its replays instead of eager launches")
+    ap.add_argument("--hold", type=float, default=0.0,
+                    help="utility mode: repeat the verification pass alone for this many seconds and exit, so that an "
+                         "external tool (rocm-smi --showclocks) can sample the clock the kernel runs at")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run an elementwise kernel that reads 1 GiB and writes 1 GiB (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -142,6 +145,16 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.hold > 0:
+        t_start, calls = time.time(), 0
+        while time.time() - t_start < args.hold:
+            for x in layers:
+                do_verify(x)
+            torch.cuda.synchronize()
+            calls += len(layers)
+        print("bench.py --hold: %s, %d verification passes in %.1f s, %.1f us each"
+              % (cfg.name, calls, time.time() - t_start, (time.time() - t_start) / calls * 1e6), flush=True)
+        return
     run_step = step
     if args.graph:   # the calls allocate nothing and never synchronise, so a step can be captured as it is
         side = torch.cuda.Stream()
