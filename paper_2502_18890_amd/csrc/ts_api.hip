@@ -121,16 +121,21 @@ bool ts::verify_shape(int n_rows, int variant, VerifyShape *out)
     const int tiles = (n_rows + 383) / 384;
     const int r = ((n_rows + tiles - 1) / tiles + 31) / 32 * 32;   // rows per tile, balanced
     if (r <= 32) *out = variant == 2 ? VerifyShape{kWide_1x1b, 32, 2} : VerifyShape{kWide_1x1, 32, 3};
-    else if (r <= 64) *out = VerifyShape{kWide_1x2, 64, 2};
+    else if (r <= 64) *out = variant == 1 ? VerifyShape{kWide_1x2h, 64, 2} : VerifyShape{kWide_1x2, 64, 2};
     else if (r <= 128) {
-        if (variant == 2) *out = VerifyShape{kWide_1x4, 128, 2};
-        else if (variant == 3) *out = VerifyShape{kWide_1x4k2, 128, 1};
+        if (variant == 1) *out = VerifyShape{kWide_1x4h, 128, 2};
+        else if (variant == 2) *out = VerifyShape{kWide_1x4, 128, 2};
+        else if (variant == 3) *out = VerifyShape{kWide_1x4k2h, 128, 1};
         else *out = VerifyShape{kWide_1x4k3, 128, 1};
-    } else if (r <= 256) *out = VerifyShape{variant == 2 ? kWide_2x4 : kWide_1x8, 256, 1};
-    else {
-        if (variant == 2) *out = VerifyShape{kWide_3x4q, 384, 1};
+    } else if (r <= 256) {
+        if (variant == 1) *out = VerifyShape{kWide_1x8, 256, 1};
+        else if (variant == 2) *out = VerifyShape{kWide_2x4, 256, 1};
+        else *out = VerifyShape{kWide_1x8h, 256, 1};
+    } else {
+        if (variant == 1) *out = r <= 320 ? VerifyShape{kWide_1x10, 320, 1} : VerifyShape{kWide_1x12, 384, 1};
+        else if (variant == 2) *out = VerifyShape{kWide_3x4q, 384, 1};
         else if (variant == 3) *out = VerifyShape{kWide_3x4, 384, 1};
-        else *out = r <= 320 ? VerifyShape{kWide_1x10, 320, 1} : VerifyShape{kWide_1x12, 384, 1};
+        else *out = r <= 320 ? VerifyShape{kWide_1x10h, 320, 1} : VerifyShape{kWide_1x12h, 384, 1};
     }
     out->rows_per_wg = r;
     return true;

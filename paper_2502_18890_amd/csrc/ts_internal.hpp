@@ -45,6 +45,13 @@ enum VerifyKernelId {
     kWide_3x4q,       // query fragments in LDS
     kWide_1x10,       // query fragments in LDS
     kWide_1x12,       // query fragments in LDS
+    // the same shapes with the second product in fp16 wherever the values fit
+    kWide_1x2h,
+    kWide_1x4h,
+    kWide_1x4k2h,
+    kWide_1x8h,
+    kWide_1x10h,
+    kWide_1x12h,
 };
 struct VerifyShape {
     int kernel_id;

@@ -52,12 +52,15 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 
 constexpr int kTileKeys = 32;
 constexpr int kStageBytes = kTileKeys * 512;   // K half then V half
 constexpr int kVHalf = kTileKeys * 256;
 constexpr int kQRowBytes = 272;                // padded query rows (QLDS)
 constexpr float kRescaleSlack = 8.0f;          // log2 units
+constexpr float kHalfShift = 6.0f;             // fp16 weights are taken 2^6 above the reference: at most 2^14, flushed below 2^-30 of that
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
@@ -84,16 +87,27 @@ constexpr int loads_per_wave(int wr) { return wr >= 16 ? 1 : (wr >= 8 ? 2 : (wr 
 // NRB: 32-row blocks per wavefront; WR: wavefronts per key group (along the query rows); KG: key
 // groups; NS: LDS stages per key group (one tile resident, the others in flight); OCC:
 // wavefronts per SIMD the register budget is cut for; QLDS: query fragments live in LDS instead
-// of registers.
-template <int NRB, int WR, int KG, int NS, int OCC, bool QLDS>
+// of registers; HALF: the second product runs in fp16 where the values allow it (see below).
+//
+// HALF.  With bf16 weights the second product needs two passes (weights and their rounding
+// residuals) to stay inside the error bar; fp16 weights (11 bits) need one, a third less matrix
+// work in a kernel whose clock is limited by power.  V is bf16 in HBM, so the value half of a tile
+// is converted to fp16 in LDS, in place, one step before the tile is consumed (each wavefront
+// converts a slice; two tiles are resident instead of one).  bf16 -> fp16 is exact for magnitudes
+// in [2^-14, 65504].  Smaller ones keep an absolute error below 2^-25, harmless next to a
+// neighbour of normal size; larger ones, NaN, and tokens whose 8-value pieces are non-zero but
+// wholly below 2^-14 do not fit.  A workgroup that meets such a value finishes its fp16 pass,
+// finds the note its wavefronts left in LDS, and runs its range again with bf16 weights and
+// residuals: the result never depends on fp16's range, and workgroups that meet no such value
+// pay one barrier for the check.
+template <int NRB, int WR, int KG, int NS, int OCC, bool QLDS, bool HALF>
 __global__ void __launch_bounds__(64 * WR * KG) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 verify_wide_kernel(const VerifyParams p)
 {
     constexpr int NT = 64 * WR * KG;
     constexpr int LPW = loads_per_wave(WR);   // load instructions per loading wavefront per tile (16 x 1 KiB = one tile)
-    constexpr int RES = 1;                    // tiles resident in LDS while the others are in flight
-    static_assert(NS >= RES + 1, "bad shape");
-    static_assert((NS - RES - 1) * LPW <= 63, "too many loads in flight for vmcnt");
+    static_assert(NS >= (HALF ? 3 : 2), "bad shape");
+    static_assert((NS - 2) * LPW <= 63, "too many loads in flight for vmcnt");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const int tid = threadIdx.x;
@@ -125,13 +139,6 @@ verify_wide_kernel(const VerifyParams p)
         t_end = t_begin + p.split_len < p.n_tokens ? t_begin + p.split_len : p.n_tokens;
     }
 
-    // ---- clear the ring --------------------------------------------------------------------
-    {
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        for (int off = tid * 16; off < KG * NS * kStageBytes; off += NT * 16) *reinterpret_cast<u32x4 *>(lds + off) = z;
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS traffic only
-
     // ---- rows of this wavefront: 32-row blocks wave, wave + WR, ... of the workgroup's row tile ----
     const int tile_row0 = blockIdx.z * p.rows_per_wg;
     const int tile_rows = (p.n_rows - tile_row0) < p.rows_per_wg ? (p.n_rows - tile_row0) : p.rows_per_wg;
@@ -162,16 +169,6 @@ verify_wide_kernel(const VerifyParams p)
 
     float m_run[NRB], l_run[NRB];
     f32x16 oacc[NRB][4];
-#pragma unroll
-    for (int rb = 0; rb < NRB; ++rb) {
-        m_run[rb] = kNegBig;
-        l_run[rb] = 0.f;
-#pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[rb][cb][e] = 0.f;
-    }
-
     // ---- HBM -> LDS -------------------------------------------------------------------------
     // Load instruction ii (0..15) of a tile fills LDS block ii: K rows 4ii..4ii+3 for ii < 8,
     // V rows 4(ii-8).. for ii >= 8.  Wavefront `wave` of a key group issues ii = wave*LPW ..
@@ -192,11 +189,11 @@ verify_wide_kernel(const VerifyParams p)
     constexpr uint32_t kRingBytes = NS * KG * kStageBytes;
     const uint32_t stage0 = kg * kStageBytes;
     const int64_t tile_elems = (int64_t)KG * kTileKeys * tstride;      // elements between consecutive group tiles
-    const uint16_t *kfill = kbase + (t_begin + (int64_t)kg * kTileKeys) * tstride;
-    const uint16_t *vfill = vbase + (t_begin + (int64_t)kg * kTileKeys) * tstride;
-    // bytes from the first row of the next tile to fill up to the end of the last valid row (<= 0: none)
-    int64_t fill_rem = (t_end - (t_begin + (int64_t)kg * kTileKeys) - 1) * tstride * 2 + 256;
-    uint32_t fill_stage = stage0;
+    const uint16_t *kfill, *vfill;
+    int64_t fill_rem;          // bytes from the first row of the next tile to fill up to the end of the last valid row (<= 0: none)
+    uint32_t fill_stage;
+    uint32_t use_stage;        // stage of the group tile being consumed
+    int64_t t0_cur;            // its first token
     auto issue_tile = [&]() {
         if (loader) {
             const uint32_t nrec = fill_rem <= 0 ? 0u : (fill_rem > 0xffffffffLL ? 0xffffffffu : (uint32_t)fill_rem);
@@ -236,8 +233,39 @@ verify_wide_kernel(const VerifyParams p)
 
     const int64_t n_tiles = (t_end - t_begin + kTileKeys - 1) / kTileKeys;
     const int n_steps = (int)((n_tiles + KG - 1) / KG);   // group tiles per key group (some groups may run one empty)
+    // ---- start of a pass over the range (a workgroup makes one, or two if fp16 did not fit) ----
+    constexpr int kLdsUsed = KG * NS * kStageBytes + (QLDS ? 32 * NRB * WR * kQRowBytes : 0);
+    uint32_t *unfit_note = reinterpret_cast<uint32_t *>(lds + kLdsUsed);   // 16 bytes behind everything else
+    auto pass_begin = [&](auto half_tag, bool first) {
+        constexpr int RES = decltype(half_tag)::value ? 2 : 1;   // tiles resident in LDS while the others are in flight
+        // clear the ring: a stage must never hold anything but finite values (a masked key adds
+        // 0 * V), whatever an earlier pass or workgroup left there
+        {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            for (int off = tid * 16; off < KG * NS * kStageBytes; off += NT * 16) *reinterpret_cast<u32x4 *>(lds + off) = z;
+            if (first && tid == 0) *unfit_note = 0u;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS traffic only
 #pragma unroll
-    for (int s = 0; s < NS - RES; ++s) issue_tile();   // tiles past the range load nothing but still count
+        for (int rb = 0; rb < NRB; ++rb) {
+            m_run[rb] = kNegBig;
+            l_run[rb] = 0.f;
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) oacc[rb][cb][e] = 0.f;
+        }
+        kfill = kbase + (t_begin + (int64_t)kg * kTileKeys) * tstride;
+        vfill = vbase + (t_begin + (int64_t)kg * kTileKeys) * tstride;
+        fill_rem = (t_end - (t_begin + (int64_t)kg * kTileKeys) - 1) * tstride * 2 + 256;
+        fill_stage = stage0;
+        use_stage = stage0;
+        t0_cur = t_begin + (int64_t)kg * kTileKeys;
+#pragma unroll
+        for (int s = 0; s < NS - RES; ++s) issue_tile();   // tiles past the range load nothing but still count
+    };
+    if constexpr (HALF) pass_begin(std::true_type{}, true);
+    else pass_begin(std::false_type{}, true);
 
     // Now wait for the query and mask loads (older than every tile load, so the tile loads stay
     // in flight) -- here, not at their first use inside the main loop, where the wait would be
@@ -292,9 +320,10 @@ verify_wide_kernel(const VerifyParams p)
     // ---- softmax of one tile's logits and O^T += V^T . P^T ----------------------------------------
     // RAGGED tiles (the last one of a range, every tile of the tree split) mask keys; full tiles
     // carry no masking code.
-    auto pv_tile = [&](auto live_tag, auto ragged_tag, const unsigned char *stage, int64_t t0, auto &sacc) {
+    auto pv_tile = [&](auto live_tag, auto ragged_tag, auto half_tag, const unsigned char *stage, int64_t t0, auto &sacc) {
         constexpr int L = decltype(live_tag)::value;
         constexpr bool RAGGED = decltype(ragged_tag)::value;
+        constexpr bool F16 = decltype(half_tag)::value;
 
         // V^T operands: vt[cb][s] = column 32*cb + n32, keys 4*hh + 16*s + 8*(e/4) + e%4 (e = 0..7).
         // The sixteen transposed reads and their wait are one asm block: issued through the
@@ -390,78 +419,152 @@ verify_wide_kernel(const VerifyParams p)
             float pe[16], psum = 0.f;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                pe[e] = fast_exp2(fmaf(sacc[rb][e], p.scale_log2, -m_run[rb]));
+                pe[e] = fast_exp2(fmaf(sacc[rb][e], p.scale_log2, (F16 ? kHalfShift : 0.f) - m_run[rb]));
                 psum += pe[e];
             }
             l_run[rb] += psum;
-            bf16x8 p_hi[2], p_lo[2];
+            if constexpr (F16) {
+                f16x8 ph[2];
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
-                u32x4 hi, lo;
+                for (int s = 0; s < 2; ++s) {
+                    u32x4 w4;
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const float a = pe[8 * s + 2 * w], b = pe[8 * s + 2 * w + 1];
-                    const uint32_t hw = pack_bf16(a, b);
-                    hi[w] = hw;
-                    lo[w] = pack_bf16(a - bf16lo_to_f32(hw), b - bf16hi_to_f32(hw));
+                    for (int w = 0; w < 4; ++w) {
+                        const f32x2 two = {pe[8 * s + 2 * w], pe[8 * s + 2 * w + 1]};
+                        w4[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, f16x2));
+                    }
+                    ph[s] = __builtin_bit_cast(f16x8, w4);
                 }
-                p_hi[s] = __builtin_bit_cast(bf16x8, hi);
-                p_lo[s] = __builtin_bit_cast(bf16x8, lo);
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb)
+                        oacc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, vt[cb][s]), ph[s], oacc[rb][cb], 0, 0, 0);
+            } else {
+                bf16x8 p_hi[2], p_lo[2];
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    u32x4 hi, lo;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        const float a = pe[8 * s + 2 * w], b = pe[8 * s + 2 * w + 1];
+                        const uint32_t hw = pack_bf16(a, b);
+                        hi[w] = hw;
+                        lo[w] = pack_bf16(a - bf16lo_to_f32(hw), b - bf16hi_to_f32(hw));
+                    }
+                    p_hi[s] = __builtin_bit_cast(bf16x8, hi);
+                    p_lo[s] = __builtin_bit_cast(bf16x8, lo);
+                }
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb) {
+                        oacc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[cb][s], p_hi[s], oacc[rb][cb], 0, 0, 0);
+                        oacc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[cb][s], p_lo[s], oacc[rb][cb], 0, 0, 0);
+                    }
             }
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-#pragma unroll
-                for (int cb = 0; cb < 4; ++cb) {
-                    oacc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[cb][s], p_hi[s], oacc[rb][cb], 0, 0, 0);
-                    oacc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[cb][s], p_lo[s], oacc[rb][cb], 0, 0, 0);
-                }
         }
     };
 
-    // Main loop over group tiles u = 0 .. n_steps-1 (tile u*KG + kg of the range): one group tile
-    // resident, NS-1 in flight.  Every wavefront of the workgroup runs the same number of steps
+    // Main loop over group tiles u = 0 .. n_steps-1 (tile u*KG + kg of the range): RES group tiles
+    // resident, NS-RES in flight.  Every wavefront of the workgroup runs the same number of steps
     // (one barrier each), whichever instantiation of the body it takes.
     const int n_full_steps = is_tree ? 0 : (int)(((t_end - t_begin) / kTileKeys) / KG);   // steps whose tiles are full for every key group
-    uint32_t use_stage = stage0;                                   // stage of the group tile being consumed
-    int64_t t0_cur = t_begin + (int64_t)kg * kTileKeys;            // its first token
-    auto sync_and_refill = [&]() {
-        // this wavefront's pieces of the next group tile have landed: the NS-RES-1 issued after it
-        // may still be in flight
-        wait_vmcnt<(NS - RES - 1) * LPW>();
-        // ... and everyone's; all are done with the previous group tile.  A bare s_barrier:
-        // __syncthreads() would add a fence that waits for every outstanding load, i.e. for the
-        // whole prefetched ring.
-        if (WR * KG > 1) asm volatile("s_barrier" ::: "memory");
-        issue_tile();                                              // refills the stage the previous group tile occupied
-    };
-    auto run = [&](auto live_tag) {
-        constexpr int L = decltype(live_tag)::value;
-        f32x16 s_cur[L > 0 ? L : 1];
-        // full tiles first, then the ragged end; the tree split is all ragged
-        auto step = [&](auto ragged_tag) {
-            sync_and_refill();
-            if (L > 0) {
-                const unsigned char *stage = lds + use_stage;
-                qk_tile(live_tag, stage, s_cur);
-                pv_tile(live_tag, ragged_tag, stage, t0_cur, s_cur);
+    // fp16 pass: the value half of a landed tile goes from bf16 to fp16 in place; rows past the end
+    // of the range become zero (a masked key then adds 0 * 0).  A 16-byte piece per lane; the WR
+    // wavefronts of a key group share the 512 pieces of their group's tile.
+    bool saw_unfit = false;
+    auto convert_values = [&](unsigned char *stage, int64_t t0) {
+        const int64_t left = t_end - t0;
+        const int n_valid = left < 0 ? 0 : (left > kTileKeys ? kTileKeys : (int)left);
+        for (int pc = wave * 64 + lane; pc < kTileKeys * 16; pc += WR * 64) {
+            u32x4 *at = reinterpret_cast<u32x4 *>(stage + kVHalf + pc * 16);
+            const u32x4 raw = *at;
+            u32x4 cv = {0u, 0u, 0u, 0u};
+            if ((pc >> 4) < n_valid) {
+                float big = 0.f;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const f32x2 two = {bf16lo_to_f32(raw[w]), bf16hi_to_f32(raw[w])};
+                    // fmaxf drops a NaN operand, so NaN is tested on its own
+                    big = fmaxf(big, fmaxf(__builtin_fabsf(two[0]), __builtin_fabsf(two[1])));
+                    saw_unfit |= (two[0] != two[0]) || (two[1] != two[1]);
+                    cv[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, f16x2));
+                }
+                // 65520 and above round to infinity; a piece (8 neighbouring values of one token)
+                // that is non-zero but entirely below 2^-14 would be left with a few bits only
+                saw_unfit |= !(big < 65520.f) || (big > 0.f && big < 6.103515625e-05f);
             }
-            use_stage += KG * kStageBytes;
-            if (use_stage >= kRingBytes) use_stage = stage0;
-            t0_cur += KG * kTileKeys;
-        };
-        for (int u = 0; u < n_full_steps; ++u) step(std::false_type{});
-        for (int u = n_full_steps; u < n_steps; ++u) step(std::true_type{});
+            *at = cv;
+        }
     };
-    if (nrb_live == NRB) run(std::integral_constant<int, NRB>{});
-    else run(std::integral_constant<int, NRB - 1>{});   // round-robin dealing: never fewer than NRB-1 unless none at all
-    wait_vmcnt<0>();   // drain the loads issued past the range before LDS is reused or released
+    auto pass_main = [&](auto half_tag) {
+        constexpr bool F16 = decltype(half_tag)::value;
+        constexpr int RES = F16 ? 2 : 1;
+        auto sync_and_refill = [&]() {
+            // this wavefront's pieces of the next group tile have landed: the NS-RES-1 issued after
+            // it may still be in flight
+            wait_vmcnt<(NS - RES - 1) * LPW>();
+            // ... and everyone's; all are done with the previous group tile.  A bare s_barrier:
+            // __syncthreads() would add a fence that waits for every outstanding load, i.e. for the
+            // whole prefetched ring.
+            if (F16) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wavefront's converted values are in LDS
+            if (WR * KG > 1) asm volatile("s_barrier" ::: "memory");
+            issue_tile();                                          // refills the stage the previous group tile occupied
+        };
+        auto run = [&](auto live_tag) {
+            constexpr int L = decltype(live_tag)::value;
+            f32x16 s_cur[L > 0 ? L : 1];
+            if (F16) {   // the first tile's values are converted before the loop; the barrier of step 0 publishes them
+                sync_and_refill();
+                convert_values(lds + use_stage, t0_cur);
+            }
+            // full tiles first, then the ragged end; the tree split is all ragged
+            auto step = [&](auto ragged_tag) {
+                sync_and_refill();
+                if (F16) {   // the tile after this one has landed (two are resident): convert its values now
+                    uint32_t next_stage = use_stage + KG * kStageBytes;
+                    if (next_stage >= kRingBytes) next_stage = stage0;
+                    convert_values(lds + next_stage, t0_cur + KG * kTileKeys);
+                }
+                if (L > 0) {
+                    const unsigned char *stage = lds + use_stage;
+                    qk_tile(live_tag, stage, s_cur);
+                    pv_tile(live_tag, ragged_tag, half_tag, stage, t0_cur, s_cur);
+                }
+                use_stage += KG * kStageBytes;
+                if (use_stage >= kRingBytes) use_stage = stage0;
+                t0_cur += KG * kTileKeys;
+            };
+            for (int u = 0; u < n_full_steps; ++u) step(std::false_type{});
+            for (int u = n_full_steps; u < n_steps; ++u) step(std::true_type{});
+        };
+        if (nrb_live == NRB) run(std::integral_constant<int, NRB>{});
+        else run(std::integral_constant<int, NRB - 1>{});   // round-robin dealing: never fewer than NRB-1 unless none at all
+        wait_vmcnt<0>();   // drain the loads issued past the range before LDS is reused or released
+    };
+    float m_shift = 0.f;   // how far above the reference point the weights of the pass that counts were taken
+    if constexpr (HALF) {
+        pass_main(std::true_type{});
+        // did any wavefront of this workgroup meet a value that fp16 cannot hold?
+        if (__builtin_amdgcn_ballot_w64(saw_unfit) != 0ull && lane == 0) *unfit_note = 1u;
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (*unfit_note != 0u) {   // the same for every wavefront: run the range again with bf16 weights
+            pass_begin(std::false_type{}, false);
+            pass_main(std::false_type{});
+        } else {
+            m_shift = kHalfShift;
+        }
+    } else {
+        pass_main(std::false_type{});
+    }
 
     // ---- merge the key groups: groups 1.. hand (m, l, O) to group 0 through LDS ----------------
     // Each lane parks exactly the accumulator elements that the lane with the same position in
     // group 0 owns, so the exchange is lane-to-lane (no transposition); 16-byte piece e of a lane
     // sits at piece (e ^ n32') of its row to keep the banks apart.  One 32-row block at a time.
     constexpr int kBlkBytes = 32 * 512;                         // one block of O: 32 rows x 128 fp32
-    constexpr int kLdsTotal = KG * NS * kStageBytes + (QLDS ? 32 * NRB * WR * kQRowBytes : 0);
+    constexpr int kLdsTotal = kLdsUsed;
     constexpr int kMlBytes = WR * 64 * 8;                       // (m, l) per lane of the parked blocks
     static_assert(KG == 1 || WR * kBlkBytes + kMlBytes <= kLdsTotal, "key-group merge staging must fit in LDS");
     if (KG > 1) {
@@ -517,7 +620,7 @@ verify_wide_kernel(const VerifyParams p)
                 const int row_base = tile_row0 + (rb * WR + wave) * 32;
                 const float l_tot = swap32_sum(l_run[rb]);
                 if (row_base + n32 < p.n_rows && hh == 0) {
-                    f32x2 ml = {m_run[rb], l_tot};
+                    f32x2 ml = {m_run[rb] - m_shift, l_tot};
                     *reinterpret_cast<f32x2 *>(p.ws_ml + (part + row_base + n32) * 2) = ml;
                 }
                 // element e of oacc[rb][cb] is output column 32*cb + 4*hh + 8*(e/4) + e%4: four
@@ -536,23 +639,23 @@ verify_wide_kernel(const VerifyParams p)
     }
 }
 
-template <int NRB, int WR, int KG, int NS, int OCC, bool QLDS>
+template <int NRB, int WR, int KG, int NS, int OCC, bool QLDS, bool HALF = false>
 hipError_t launch_one(const VerifyParams &p, hipStream_t stream)
 {
     constexpr int kRows = 32 * NRB * WR;
-    constexpr int lds_bytes = KG * NS * kStageBytes + (QLDS ? kRows * kQRowBytes : 0);
+    constexpr int lds_bytes = KG * NS * kStageBytes + (QLDS ? kRows * kQRowBytes : 0) + 16;   // + the note of the fp16 pass
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
     static_assert(64 * WR * KG <= 1024, "workgroup size");
     if (p.rows_per_wg > kRows || p.rows_per_wg % 32 != 0) return hipErrorInvalidValue;
     static bool attr_set = false;
     if (lds_bytes > 64 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS, HALF>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(p.n_split + 1, p.n_kv_heads, (p.n_rows + p.rows_per_wg - 1) / p.rows_per_wg);
-    hipLaunchKernelGGL((verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS>), grid, dim3(64 * WR * KG), lds_bytes, stream, p);
+    hipLaunchKernelGGL((verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS, HALF>), grid, dim3(64 * WR * KG), lds_bytes, stream, p);
     return hipGetLastError();
 }
 
@@ -572,6 +675,12 @@ hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t 
         case kWide_3x4: return launch_one<3, 4, 1, 6, 1, false>(p, stream);
         case kWide_3x4q: return launch_one<3, 4, 1, 3, 1, true>(p, stream);
         case kWide_1x10: return launch_one<1, 10, 1, 4, 3, true>(p, stream);
+        case kWide_1x2h: return launch_one<1, 2, 1, 4, 2, false, true>(p, stream);
+        case kWide_1x4h: return launch_one<1, 4, 1, 4, 2, false, true>(p, stream);
+        case kWide_1x4k2h: return launch_one<1, 4, 2, 3, 2, true, true>(p, stream);
+        case kWide_1x8h: return launch_one<1, 8, 1, 6, 2, false, true>(p, stream);
+        case kWide_1x10h: return launch_one<1, 10, 1, 4, 3, true, true>(p, stream);
+        case kWide_1x12h: return launch_one<1, 12, 1, 3, 3, true, true>(p, stream);
         case kWide_1x12: return launch_one<1, 12, 1, 3, 3, true>(p, stream);
         default: return hipErrorInvalidValue;
     }

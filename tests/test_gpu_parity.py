@@ -270,6 +270,35 @@ def test_verify_kernel_variants(ts, variant, hq, hkv, n, t):
     assert_close(lse, rlse, "verify lse variant=%d" % variant)
 
 
+@pytest.mark.parametrize("hq,hkv,n,t", [(32, 8, 2085, 64), (40, 8, 700, 64), (16, 4, 900, 32), (48, 8, 333, 64), (8, 2, 500, 32)])
+@pytest.mark.parametrize("kind", ["huge", "tiny"])
+@pytest.mark.parametrize("variant", [0, 1, 3])
+def test_verify_values_outside_half_range(ts, variant, kind, hq, hkv, n, t):
+    """For more than 32 rows per KV head the weights meet V in fp16 when V fits.  Values that do
+    not fit -- magnitudes of 65520 and more, or tokens whose values all lie below 2^-14 -- must
+    be caught and take the bf16 route: the result still matches the oracle, relative to the size
+    of the output."""
+    if kind == "tiny":
+        c = _case(31, hq, hkv, n, t, vscale=2.0 ** -30)
+    else:
+        c = _case(31, hq, hkv, n, t)
+        big = S.f32_to_bf16_bits(np.array([131072.0, -1.0e30, 65536.0], dtype=np.float32))
+        rng = c["rng"]
+        for arr in (c["v"], c["v_tree"]):
+            flat = arr.reshape(-1)
+            where = rng.choice(flat.size, size=7, replace=False)
+            flat[where] = big[rng.integers(0, 3, size=7)]
+    parent = _random_parent(c["rng"], t)
+    try:
+        ts.tune_set("verify_variant", variant)   # 1 and 3 select fp16 shapes for 64 and 128 rows too
+        out, lse, ref, rlse = _verify_both(ts, c, parent)
+    finally:
+        ts.tune_set("verify_variant", 0)
+    size = max(1.0, float(np.max(np.abs(ref))))
+    assert_close(out / size, ref / size, "verify out, %s values" % kind)
+    assert_close(lse, rlse, "verify lse, %s values" % kind)
+
+
 @pytest.mark.parametrize("kind", ["chain", "star", "deep-wide"])
 def test_verify_wide_trees(ts, kind):
     """Trees of more than 64 nodes (the paper's 40-node tree plus up to 60 retrieved n-gram
