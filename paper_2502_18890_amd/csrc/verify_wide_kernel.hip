@@ -677,7 +677,7 @@ hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t 
         case kWide_1x10: return launch_one<1, 10, 1, 4, 3, true>(p, stream);
         case kWide_1x2h: return launch_one<1, 2, 1, 4, 2, false, true>(p, stream);
         case kWide_1x4h: return launch_one<1, 4, 1, 4, 2, false, true>(p, stream);
-        case kWide_1x4k2h: return launch_one<1, 4, 2, 3, 2, true, true>(p, stream);
+        case kWide_1x4k2h: return launch_one<1, 4, 2, 4, 2, false, true>(p, stream);
         case kWide_1x8h: return launch_one<1, 8, 1, 6, 2, false, true>(p, stream);
         case kWide_1x10h: return launch_one<1, 10, 1, 4, 3, true, true>(p, stream);
         case kWide_1x12h: return launch_one<1, 12, 1, 3, 3, true, true>(p, stream);
