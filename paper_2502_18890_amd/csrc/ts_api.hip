@@ -106,7 +106,9 @@ bool partial_chunk_ok(int chunk_size) { return chunk_size >= 16 && chunk_size <=
 // Kernel shape by number of query rows per KV head.  Up to 32 rows the pass is purely HBM-bound
 // and the 16x16x32 kernel with its small workgroups (many of them per CU) is used; beyond that
 // the 32x32x16 kernel, in row tiles of at most 384 rows.  Defaults are the fastest measured
-// shapes; variant 1..3 select the alternatives (all produce the same results).
+// shapes; variant 1..3 select alternatives where there are any (all produce the same results):
+// 1 swaps the precision of the second product (fp16 where the default is bf16 + residual and
+// the other way round), 2 and 3 other workgroup shapes.
 bool ts::verify_shape(int n_rows, int variant, VerifyShape *out)
 {
     if (n_rows < 1 || n_rows > TS_MAX_GROUP * TS_MAX_TREE) return false;
@@ -133,8 +135,6 @@ bool ts::verify_shape(int n_rows, int variant, VerifyShape *out)
         else *out = VerifyShape{kWide_1x8h, 256, 1};
     } else {
         if (variant == 1) *out = r <= 320 ? VerifyShape{kWide_1x10, 320, 1} : VerifyShape{kWide_1x12, 384, 1};
-        else if (variant == 2) *out = VerifyShape{kWide_3x4q, 384, 1};
-        else if (variant == 3) *out = VerifyShape{kWide_3x4, 384, 1};
         else *out = r <= 320 ? VerifyShape{kWide_1x10h, 320, 1} : VerifyShape{kWide_1x12h, 384, 1};
     }
     out->rows_per_wg = r;

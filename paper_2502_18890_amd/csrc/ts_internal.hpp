@@ -37,12 +37,9 @@ enum VerifyKernelId {
     kWide_1x1b,       // deeper ring, two workgroups per CU
     kWide_1x2,
     kWide_1x4,
-    kWide_1x4k2,      // two key groups, query fragments in LDS
     kWide_1x4k3,      // three key groups, query fragments in LDS
     kWide_2x4,
     kWide_1x8,
-    kWide_3x4,
-    kWide_3x4q,       // query fragments in LDS
     kWide_1x10,       // query fragments in LDS
     kWide_1x12,       // query fragments in LDS
     // the same shapes with the second product in fp16 wherever the values fit

@@ -668,12 +668,9 @@ hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t 
         case kWide_1x1b: return launch_one<1, 1, 1, 4, 2, false>(p, stream);
         case kWide_1x2: return launch_one<1, 2, 1, 4, 2, false>(p, stream);
         case kWide_1x4: return launch_one<1, 4, 1, 4, 2, false>(p, stream);
-        case kWide_1x4k2: return launch_one<1, 4, 2, 3, 2, true>(p, stream);
         case kWide_1x4k3: return launch_one<1, 4, 3, 2, 3, true>(p, stream);
         case kWide_2x4: return launch_one<2, 4, 1, 6, 1, false>(p, stream);
         case kWide_1x8: return launch_one<1, 8, 1, 6, 2, false>(p, stream);
-        case kWide_3x4: return launch_one<3, 4, 1, 6, 1, false>(p, stream);
-        case kWide_3x4q: return launch_one<3, 4, 1, 3, 1, true>(p, stream);
         case kWide_1x10: return launch_one<1, 10, 1, 4, 3, true>(p, stream);
         case kWide_1x2h: return launch_one<1, 2, 1, 4, 2, false, true>(p, stream);
         case kWide_1x4h: return launch_one<1, 4, 1, 4, 2, false, true>(p, stream);
