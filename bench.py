@@ -238,11 +238,13 @@ def main():
     kernel_name = "verify_dma_kernel (16x16x32 MFMA)" if cfg.group * t <= 32 else "verify_wide_kernel (32x32x16 MFMA)"
 
     us_per_layer_step = ms_per_step * 1e3 / n_layers
+    # from 256 query rows per KV head on, the verification pass multiplies fp16 weights with fp16 values
+    dtype = "bf16 inputs, fp32 accumulate" if cfg.group * t < 256 else "bf16 inputs, fp32 accumulate (weights x values of the verification pass in fp16)"
     res = {
         "metric": "us per layer-step: chunk scores + top-k + partial-KV attention + tree-verify attention over the full cache",
         "value": round(us_per_layer_step, 3), "unit": "us/layer-step", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16 inputs, fp32 accumulate", "data": "synthetic",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": "%s: %d q heads / %d kv heads, d=128, N=%d cached tokens, chunk %d, top-k %d+%d chunks, tree %d nodes, %d layer caches, batch 1" % (
             cfg.name, hq, hkv, n, cfg.chunk, cfg.k, cfg.n_sink, t, n_layers), "config_index": args.config,
             "layers": n_layers, "n_tokens": n, "launch": "hip graph replay" if args.graph else "eager"},
