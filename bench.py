@@ -238,8 +238,8 @@ def main():
     kernel_name = "verify_dma_kernel (16x16x32 MFMA)" if cfg.group * t <= 32 else "verify_wide_kernel (32x32x16 MFMA)"
 
     us_per_layer_step = ms_per_step * 1e3 / n_layers
-    # from 256 query rows per KV head on, the verification pass multiplies fp16 weights with fp16 values
-    dtype = "bf16 inputs, fp32 accumulate" if cfg.group * t < 256 else "bf16 inputs, fp32 accumulate (weights x values of the verification pass in fp16)"
+    # beyond 128 query rows per KV head the verification pass multiplies fp16 weights with fp16 values
+    dtype = "bf16 inputs, fp32 accumulate" if cfg.group * t <= 128 else "bf16 inputs, fp32 accumulate (weights x values of the verification pass in fp16)"
     res = {
         "metric": "us per layer-step: chunk scores + top-k + partial-KV attention + tree-verify attention over the full cache",
         "value": round(us_per_layer_step, 3), "unit": "us/layer-step", "n_gpus": 1, "steps": args.steps,
