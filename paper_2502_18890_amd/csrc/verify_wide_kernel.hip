@@ -37,7 +37,7 @@
 //   V rows: LDS piece pos of row R holds global piece pos ^ 4*(R mod 4)  (the four keys a
 //           transposed read touches land in four different 64-byte bank groups).
 // Rows past the end of a range are cut off by the buffer descriptor's byte count; the ring is
-// cleared once so a stage never holds anything but finite values (a masked key adds 0 * V).
+// cleared before a pass so a stage never holds anything but finite values (a masked key adds 0 * V).
 #include <type_traits>
 
 #include "ts_device.hpp"
@@ -85,7 +85,7 @@ __device__ __forceinline__ float swap32_sum(float x)
 constexpr int loads_per_wave(int wr) { return wr >= 16 ? 1 : (wr >= 8 ? 2 : (wr >= 4 ? 4 : (wr >= 2 ? 8 : 16))); }
 
 // NRB: 32-row blocks per wavefront; WR: wavefronts per key group (along the query rows); KG: key
-// groups; NS: LDS stages per key group (one tile resident, the others in flight); OCC:
+// groups; NS: LDS stages per key group (one tile resident, two with HALF, the others in flight); OCC:
 // wavefronts per SIMD the register budget is cut for; QLDS: query fragments live in LDS instead
 // of registers; HALF: the second product runs in fp16 where the values allow it (see below).
 //
