@@ -482,18 +482,20 @@ verify_wide_kernel(const VerifyParams p)
             const u32x4 raw = *at;
             u32x4 cv = {0u, 0u, 0u, 0u};
             if ((pc >> 4) < n_valid) {
-                float big = 0.f;
+                // largest magnitude of the piece as a bf16 bit pattern (patterns order like the
+                // values; infinity and NaN sort above every finite value)
+                uint32_t big = 0u;
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
+                    const uint32_t mag = raw[w] & 0x7fff7fffu;
+                    big = max(big, max(mag >> 16, mag & 0xffffu));
                     const f32x2 two = {bf16lo_to_f32(raw[w]), bf16hi_to_f32(raw[w])};
-                    // fmaxf drops a NaN operand, so NaN is tested on its own
-                    big = fmaxf(big, fmaxf(__builtin_fabsf(two[0]), __builtin_fabsf(two[1])));
-                    saw_unfit |= (two[0] != two[0]) || (two[1] != two[1]);
                     cv[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, f16x2));
                 }
-                // 65520 and above round to infinity; a piece (8 neighbouring values of one token)
-                // that is non-zero but entirely below 2^-14 would be left with a few bits only
-                saw_unfit |= !(big < 65520.f) || (big > 0.f && big < 6.103515625e-05f);
+                // fits: zero, or between 2^-14 (0x3880) and 65280 (0x477f, the largest bf16 below
+                // 65520, where fp16 rounds to infinity).  A piece (8 neighbouring values of one
+                // token) that is non-zero but entirely below 2^-14 would be left with a few bits only.
+                saw_unfit |= big != 0u && (big - 0x3880u) >= (0x4780u - 0x3880u);
             }
             *at = cv;
         }
