@@ -5,7 +5,11 @@
 One step = one pass of the whole path (chunk scores -> top-k -> partial-KV attention -> tree
 verification) over every layer's own cache of the workload; caches are resident in HBM before
 the timed region and each layer has its own, so every launch reads cold data.  Prints one
-JSON line; see the design doc for the definitions of the fields.
+JSON line: `value` is microseconds per layer-step (all four calls, one layer's cache);
+`roofline` is the split kernel of the verification pass, its algorithmic bytes (K and V of the
+cache and tree, queries, outputs) over its average duration from HIP events, against 8 TB/s;
+`roofline_mfma` the same kernel's algorithmic flops; `cpu_baseline` the fp64 oracle timed on the
+host cores over one layer's cache.
 """
 import argparse
 import json
