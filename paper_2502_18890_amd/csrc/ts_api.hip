@@ -88,7 +88,7 @@ struct PartialPlan {
 void plan_partial(int n_q_heads, int n_kv_heads, int n_sel, int chunk_size, PartialPlan *pl)
 {
     const int group = n_q_heads / n_kv_heads;
-    pl->segs_per_chunk = chunk_size / 16;
+    pl->segs_per_chunk = chunk_size / 8;
     pl->n_seg = n_sel * pl->segs_per_chunk;
     pl->n_part = (pl->n_seg + 15) / 16;
     const size_t rows_total = (size_t)n_kv_heads * pl->n_part * group;

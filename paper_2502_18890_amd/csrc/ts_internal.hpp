@@ -71,7 +71,7 @@ struct PartialParams {
     int64_t n_tokens;
     int n_q_heads, n_kv_heads, group;
     int n_sel, chunk_size;
-    int segs_per_chunk;       // chunk_size / 16: a 16-lane row handles one 16-token segment
+    int segs_per_chunk;       // chunk_size / 8: a 16-lane row handles one 8-token segment
     int n_seg;                // n_sel * segs_per_chunk
     int n_part;               // workgroups per KV head = ceil(n_seg / 16), one partial each
     float scale_log2;
