@@ -8,8 +8,9 @@
 //   1. radix select, 8 bits per pass from the top: a 256-bin LDS histogram of the candidates
 //      that still match the decided prefix, one wavefront scans it from the top bin down and
 //      fixes the next digit of the k-th largest key.  Digits that are the same for all keys
-//      (the upper bytes of ~index) are skipped: 4 passes for the score + 1..3 for the index,
-//      and the index passes are skipped too unless equal scores straddle the cut.
+//      (the upper bytes of ~index) are skipped: at most 4 passes for the score + 1..3 for the
+//      index; the passes stop as soon as the bin of the k-th largest key holds exactly the
+//      keys still wanted (typically after two or three digits of the score).
 //   2. the k keys >= the k-th largest are compacted into LDS (slot order is arbitrary);
 //   3. they are put in order: by rank counting (k <= 256: each key counts the larger ones,
 //      all reads are LDS broadcasts) or by a bitonic network in LDS (larger k).
@@ -106,9 +107,10 @@ __global__ void __launch_bounds__(1024) topk_kernel(const TopkParams p, int n_so
         prefix |= (uint64_t)ctl[0] << shift;
         mask |= 0xffull << shift;
         kk = ctl[1];
-        // The score is decided and every key that shares the k-th largest score is wanted: no tie
-        // straddles the cut, so the index digits need not be examined.
-        if (pass == 3 && ctl[3] == kk) break;
+        // Every key that shares the digits decided so far with the k-th largest is wanted: nothing
+        // straddles the cut, so the remaining digits (of the score, and the index digits that
+        // break ties) need not be examined.
+        if (ctl[3] == kk) break;
     }
 
     // ---- 2. compact the k keys >= the k-th largest -------------------------------------------
