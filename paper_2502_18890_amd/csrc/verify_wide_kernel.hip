@@ -60,6 +60,7 @@ constexpr int kStageBytes = kTileKeys * 512;   // K half then V half
 constexpr int kVHalf = kTileKeys * 256;
 constexpr int kQRowBytes = 272;                // padded query rows (QLDS)
 constexpr float kRescaleSlack = 8.0f;          // log2 units
+constexpr float kResidualShare = 1.0f / 8.0f;    // share of a row's running denominator from which a weight counts as concentrated
 constexpr float kHalfShift = 6.0f;             // fp16 weights are taken 2^6 above the reference: at most 2^14, flushed below 2^-30 of that
 
 template <int N>
@@ -413,7 +414,22 @@ verify_wide_kernel(const VerifyParams p)
             }
         }
 
-        // P = exp2(scale*s - m), split hi + lo (both bf16), O^T += V^T . P^T
+        // fp16 weights carry 11 bits.  That is enough where a row's weight is spread over many keys
+        // (independent rounding errors of 2^-12 each), not where a few keys hold it: a tile in
+        // which some row's largest weight reaches kResidualShare of what that row has accumulated
+        // so far also multiplies the rounding residuals (fp16 again, 22 bits in all).  That second
+        // product sits in a loop that runs zero or one times rather than in a branch:
+        // accumulators updated inside an if get copied at the join, loop-carried ones stay put.
+        int n_trips = 1;
+        if constexpr (F16) {
+            bool concentrated = false;
+#pragma unroll
+            for (int rb = 0; rb < L; ++rb)
+                concentrated |= fast_exp2(m_tile[rb] - m_run[rb] + kHalfShift) >= kResidualShare * l_run[rb];
+            n_trips = __builtin_amdgcn_ballot_w64(concentrated) != 0ull ? 2 : 1;
+        }
+
+        // P = exp2(scale*s - m); O^T += V^T . P^T with P in fp16, or split hi + lo (both bf16)
 #pragma unroll
         for (int rb = 0; rb < L; ++rb) {
             float pe[16], psum = 0.f;
@@ -440,6 +456,30 @@ verify_wide_kernel(const VerifyParams p)
 #pragma unroll
                     for (int cb = 0; cb < 4; ++cb)
                         oacc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, vt[cb][s]), ph[s], oacc[rb][cb], 0, 0, 0);
+#pragma clang loop unroll(disable)
+                for (int trip = 1; trip < n_trips; ++trip) {   // zero or one times
+                    // weights of the second product: what rounding to fp16 left behind
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        u32x4 w4;
+#pragma unroll
+                        for (int w = 0; w < 4; ++w) {
+                            // (halves taken as scalars: a bit_cast of one vector element to a
+                            // two-element fp16 vector was seen compiled as element 0 for every w)
+                            const uint32_t had = __builtin_bit_cast(u32x4, ph[s])[w];
+                            const float had_lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(had & 0xffffu));
+                            const float had_hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(had >> 16));
+                            const f32x2 left = {pe[8 * s + 2 * w] - had_lo, pe[8 * s + 2 * w + 1] - had_hi};
+                            w4[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(left, f16x2));
+                        }
+                        ph[s] = __builtin_bit_cast(f16x8, w4);
+                    }
+#pragma unroll
+                    for (int s = 0; s < 2; ++s)
+#pragma unroll
+                        for (int cb = 0; cb < 4; ++cb)
+                            oacc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, vt[cb][s]), ph[s], oacc[rb][cb], 0, 0, 0);
+                }
             } else {
                 bf16x8 p_hi[2], p_lo[2];
 #pragma unroll

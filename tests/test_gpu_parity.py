@@ -223,6 +223,33 @@ def test_verify_dominant_key_and_large_values(ts):
     assert_close(lse, rlse, "verify lse (peaked)")
 
 
+@pytest.mark.parametrize("hq,hkv,t", [(32, 8, 64), (40, 8, 64), (16, 4, 64)])
+def test_verify_dominant_key_and_large_values_wide(ts, hq, hkv, t):
+    """The same with 256 and 320 rows per KV head (the shapes whose second product runs in fp16)
+    and with 64: a key that carries nearly all the weight, values 8x larger."""
+    g = hq // hkv
+    c = _case(40, hq, hkv, 1500, t, vscale=8.0)
+    kf = S.bf16_bits_to_f32(c["k"]).copy()
+    qf = S.bf16_bits_to_f32(c["q_tree"])
+    for h in range(hkv):
+        kf[h, 321 + h] = qf[5, h * g] * (20.0 / SCALE / float(qf[5, h * g] @ qf[5, h * g]))
+    c["k"] = S.f32_to_bf16_bits(kf)
+    parent = _random_parent(c["rng"], t)
+    out, lse, ref, rlse = _verify_both(ts, c, parent)
+    assert_close(out, ref, "verify out (peaked, wide)")
+    assert_close(lse, rlse, "verify lse (peaked, wide)")
+
+
+@pytest.mark.parametrize("hq,hkv,t", [(32, 8, 64), (40, 8, 64)])
+def test_verify_few_keys_precision_wide(ts, hq, hkv, t):
+    """Few comparable keys per row at 256 and 320 rows per KV head, values 4x larger."""
+    for n in (0, 1, 3):
+        c = _case(50 + n, hq, hkv, n, t, vscale=4.0)
+        parent = _random_parent(c["rng"], t)
+        out, lse, ref, rlse = _verify_both(ts, c, parent)
+        assert_close(out, ref, "verify out (few keys, wide, n=%d)" % n)
+
+
 def test_verify_few_keys_precision(ts):
     """Two or three comparable keys per row (tiny cache): the regime where a bf16 probability
     would cost ~2^-9 of |v|."""
