@@ -156,11 +156,10 @@ template <int G>
 hipError_t launch_g(const PartialParams &p, hipStream_t stream)
 {
     constexpr int lds_bytes = kSegsPerWg * G * (kHeadDim + 2) * (int)sizeof(float);
-    static bool attr_set = false;
-    if (lds_bytes > 64 * 1024 && !attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(partial_kernel<G>), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    static std::atomic<uint64_t> lds_allowed{0};
+    if (lds_bytes > 64 * 1024) {
+        const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(partial_kernel<G>), lds_bytes, lds_allowed);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     dim3 grid(p.n_part, p.n_kv_heads);
     hipLaunchKernelGGL(partial_kernel<G>, grid, dim3(256), lds_bytes, stream, p);

@@ -166,12 +166,10 @@ hipError_t launch_topk(const TopkParams &p, hipStream_t stream)
     const int nt = n_cand <= 4096 ? 256 : 1024;
     const size_t sel_cap = p.k > kRankCountMax ? (size_t)n_sort : (size_t)p.k;
     const size_t lds_bytes = kHistBytes + kCtlBytes + sel_cap * sizeof(uint64_t) + (stage_keys ? (size_t)n_cand * sizeof(uint32_t) : 0);
-    static bool attr_set = false;
-    if (lds_bytes > 64 * 1024 && !attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(topk_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+    static std::atomic<uint64_t> lds_allowed{0};
+    if (lds_bytes > 64 * 1024) {
+        const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(topk_kernel), 128 * 1024, lds_allowed);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     hipLaunchKernelGGL(topk_kernel, dim3(p.n_kv_heads), dim3(nt), lds_bytes, stream, p, n_sort, idx_bytes, stage_keys);
     return hipGetLastError();

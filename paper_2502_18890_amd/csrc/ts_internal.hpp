@@ -2,8 +2,23 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 
 namespace ts {
+
+// Kernels that use more than 64 KiB of dynamic LDS must be told so once per device; `done` is the
+// launcher's own bit mask of devices already served (devices >= 64 are simply asked every time).
+inline hipError_t allow_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_t> &done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < 64 && ((done.load(std::memory_order_relaxed) >> dev) & 1ull)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess && dev >= 0 && dev < 64) done.fetch_or(1ull << dev, std::memory_order_relaxed);
+    return e;
+}
+
 
 // ---- tree verification (verify_dma_kernel.hip, verify_wide_kernel.hip) ----------------------
 constexpr int kMaxTree = 128;

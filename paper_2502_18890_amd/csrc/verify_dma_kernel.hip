@@ -379,12 +379,10 @@ hipError_t launch_one(const VerifyParams &p, hipStream_t stream)
     constexpr int kRows = 16 * NRB * WR;
     constexpr int lds_bytes = NS * kStageBytes + (QLDS ? kRows * kQRowBytes : 0);
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
-    static bool attr_set = false;
-    if (lds_bytes > 64 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(verify_dma_kernel<NRB, WR, NS, OCC, QLDS>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    static std::atomic<uint64_t> lds_allowed{0};
+    if (lds_bytes > 64 * 1024) {
+        const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(verify_dma_kernel<NRB, WR, NS, OCC, QLDS>), lds_bytes, lds_allowed);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     dim3 grid(p.n_split + 1, p.n_kv_heads, (p.n_rows + kRows - 1) / kRows);
     hipLaunchKernelGGL((verify_dma_kernel<NRB, WR, NS, OCC, QLDS>), grid, dim3(64 * WR), lds_bytes, stream, p);

@@ -689,12 +689,10 @@ hipError_t launch_one(const VerifyParams &p, hipStream_t stream)
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
     static_assert(64 * WR * KG <= 1024, "workgroup size");
     if (p.rows_per_wg > kRows || p.rows_per_wg % 32 != 0) return hipErrorInvalidValue;
-    static bool attr_set = false;
-    if (lds_bytes > 64 * 1024 && !attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS, HALF>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    static std::atomic<uint64_t> lds_allowed{0};
+    if (lds_bytes > 64 * 1024) {
+        const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void *>(verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS, HALF>), lds_bytes, lds_allowed);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     dim3 grid(p.n_split + 1, p.n_kv_heads, (p.n_rows + p.rows_per_wg - 1) / p.rows_per_wg);
     hipLaunchKernelGGL((verify_wide_kernel<NRB, WR, KG, NS, OCC, QLDS, HALF>), grid, dim3(64 * WR * KG), lds_bytes, stream, p);
