@@ -49,6 +49,7 @@ typedef enum {
 #define TS_MAX_GROUP 8        /* query heads per KV head */
 #define TS_MAX_CHUNKS (1 << 20)  /* chunks per KV head that ts_topk_chunks can rank */
 #define TS_MAX_TOPK 8192      /* chunks per KV head that ts_topk_chunks can select (k) */
+#define TS_MAX_STRIDE_TOKEN (1 << 24) /* largest stride_token, in elements (32 MiB between token rows) */
 
 /* One layer's KV cache, as the paper's C_full (Alg. 1): n_tokens cached (key, value) pairs
  * for each of n_kv_heads heads.  Element (h, t, x) of K lives at
@@ -60,7 +61,7 @@ typedef struct {
     int32_t n_kv_heads;
     int32_t head_dim;       /* must be TS_HEAD_DIM */
     int64_t stride_head;    /* elements; multiple of 8 */
-    int64_t stride_token;   /* elements; multiple of 8, >= head_dim */
+    int64_t stride_token;   /* elements; multiple of 8, >= head_dim, <= TS_MAX_STRIDE_TOKEN */
 } ts_kv_view;
 
 enum { TS_OP_PARTIAL_ATTN = 1, TS_OP_TREE_VERIFY = 2 };

@@ -27,6 +27,8 @@ int check_view(const ts_kv_view *kv, bool need_v, bool allow_empty)
     if (kv->n_tokens == 0) return TS_OK;
     if (!kv->k || (need_v && !kv->v)) return TS_ERR_NULL;
     if (kv->stride_token < TS_HEAD_DIM || kv->stride_head < 0) return TS_ERR_SHAPE;
+    // the attention kernels address the 32 rows of a tile with 32-bit byte offsets
+    if (kv->stride_token > TS_MAX_STRIDE_TOKEN) return TS_ERR_UNSUPPORTED;
     if ((kv->stride_token % 8) != 0 || (kv->stride_head % 8) != 0) return TS_ERR_ALIGN;
     if (!aligned16(kv->k) || (need_v && !aligned16(kv->v))) return TS_ERR_ALIGN;
     return TS_OK;

@@ -88,6 +88,7 @@ def test_scores_and_topk_reject_bad_arguments(lib, binding):
     assert cs(_view(binding, k=0x1004)) == TS_ERR_ALIGN
     assert cs(_view(binding, st=132)) == TS_ERR_ALIGN
     assert cs(_view(binding, st=64)) == TS_ERR_SHAPE
+    assert cs(_view(binding, st=(1 << 24) + 8)) == TS_ERR_UNSUPPORTED   # token rows too far apart
     tk = lambda n_chunks=10, sink=1, k=3, s=0x1000, o=0x2000: lib.ts_topk_chunks(s, 2, n_chunks, sink, k, o, None)
     assert tk(s=None) == TS_ERR_NULL and tk(o=None) == TS_ERR_NULL
     assert tk(sink=8, k=3) == TS_ERR_SHAPE
