@@ -23,6 +23,7 @@ int check_view(const ts_kv_view *kv, bool need_v, bool allow_empty)
     if (!kv) return TS_ERR_NULL;
     if (kv->head_dim != TS_HEAD_DIM) return TS_ERR_UNSUPPORTED;
     if (kv->n_kv_heads < 1) return TS_ERR_SHAPE;
+    if (kv->n_kv_heads > 65535) return TS_ERR_UNSUPPORTED;   // heads are a grid dimension
     if (kv->n_tokens < 0 || (kv->n_tokens == 0 && !allow_empty)) return TS_ERR_SHAPE;
     if (kv->n_tokens == 0) return TS_OK;
     if (!kv->k || (need_v && !kv->v)) return TS_ERR_NULL;
@@ -376,6 +377,7 @@ int ts_append_accepted(const ts_kv_view *kv, const void *k_tree, const void *v_t
     if (!kv) return TS_ERR_NULL;
     if (kv->head_dim != TS_HEAD_DIM) return TS_ERR_UNSUPPORTED;
     if (kv->n_kv_heads < 1 || kv->n_tokens < 0) return TS_ERR_SHAPE;
+    if (kv->n_kv_heads > 65535) return TS_ERR_UNSUPPORTED;
     if (!kv->k || !kv->v || !k_tree || !v_tree || !accepted) return TS_ERR_NULL;
     if (kv->stride_token < TS_HEAD_DIM || kv->stride_head < 0) return TS_ERR_SHAPE;
     if ((kv->stride_token % 8) != 0 || (kv->stride_head % 8) != 0) return TS_ERR_ALIGN;
