@@ -9,7 +9,7 @@ import ts_synth as S
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("ci", [0, 1])
+@pytest.mark.parametrize("ci", [0, 1, 4])   # 4: 320 rows per KV head, the fp16 second product
 def test_layer_step_in_a_graph_matches_eager(ci):
     import torch
     import paper_2502_18890_amd as ts
