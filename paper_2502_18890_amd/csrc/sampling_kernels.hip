@@ -169,10 +169,88 @@ __device__ __forceinline__ float block_sum16(float wave_total, float *red, int w
     return s;
 }
 
+// ---- top-p threshold ------------------------------------------------------------------------------------
+// The pool of top-p is {v : p[v] >= tau} for the largest tau whose pool holds mass >= param.  Probabilities
+// are non-negative floats, so their bit patterns order like their values and tau can be found digit by
+// digit (11 + 11 + 9 bits of the pattern, three walks over the row): every entry that matches the digits
+// decided so far adds its mass to the LDS bin of its next digit, and a scan from the top bin down finds the
+// bin in which the running mass reaches what is still wanted.  Masses are added as integers (units of
+// 2^-40, exact for p >= 2^-17, within half a unit below): integer sums do not depend on the order of the
+// atomic adds, so the same call is bit-identical every time, and the decision differs from one taken on
+// exact sums only when the mass at the cut is within vocab * 2^-41 of param.
+constexpr int kMassBins = 2048;
+
+__device__ __forceinline__ unsigned long long mass_units(float p)
+{
+    const float pc = fminf(p, 1.0f);
+    const float hi = floorf(pc * 0x1p20f);             // exact: scaling by a power of two
+    const float rem = fmaf(pc, 0x1p20f, -hi);          // exact, in [0, 1)
+    const uint32_t lo = (uint32_t)fmaf(rem, 0x1p20f, 0.5f);
+    return ((unsigned long long)(uint32_t)hi << 20) + lo;
+}
+
+__device__ float top_p_threshold(const RowWalker &w, float param, unsigned long long *hist, unsigned long long *wtot,
+                                 unsigned long long *ctl, int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    unsigned long long want = (unsigned long long)ceil((double)param * 0x1p40);
+    if (want == 0ull) want = 1ull;
+    uint32_t prefix = 0u, mask = 0u;
+#pragma unroll 1
+    for (int level = 0; level < 3; ++level) {
+        const int shift = level == 0 ? 20 : (level == 1 ? 9 : 0);
+        const int n_bins = level == 2 ? 512 : 2048;
+        for (int i = tid; i < n_bins; i += 1024) hist[i] = 0ull;
+        if (tid == 0) ctl[0] = ~0ull;
+        __syncthreads();
+        w.for_each_chunk([&](int64_t, int64_t, const float (&v)[4]) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t bits = __float_as_uint(v[e]);
+                if (v[e] > 0.f && (bits & mask) == prefix) {      // false for NaN and for the zeros past the row
+                    const unsigned long long units = mass_units(v[e]);
+                    if (units != 0ull) atomicAdd(&hist[(bits >> shift) & (uint32_t)(n_bins - 1)], units);
+                }
+            }
+        });
+        __syncthreads();
+        // thread t owns bins n_bins-1-2t and n_bins-2-2t (descending): running mass above each bin
+        unsigned long long c[2] = {0ull, 0ull};
+        if (2 * tid < n_bins) c[0] = hist[n_bins - 1 - 2 * tid], c[1] = hist[n_bins - 2 - 2 * tid];
+        const unsigned long long tot = c[0] + c[1];
+        unsigned long long incl = tot;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const unsigned long long up = __shfl_up(incl, d, 64);
+            if (lane >= d) incl += up;
+        }
+        if (lane == 63) wtot[wave] = incl;
+        __syncthreads();
+        unsigned long long above = incl - tot;
+        for (int i = 0; i < wave; ++i) above += wtot[i];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (above < want && want <= above + c[j]) {
+                ctl[0] = (unsigned long long)(n_bins - 1 - 2 * tid - j);
+                ctl[1] = want - above;
+            }
+            above += c[j];
+        }
+        __syncthreads();
+        if (ctl[0] == ~0ull) return 0.f;    // the whole row holds less than param (only at the first level): every token is in the pool
+        prefix |= (uint32_t)ctl[0] << shift;
+        mask |= (uint32_t)(n_bins - 1) << shift;
+        want = ctl[1];
+        __syncthreads();                    // ctl and hist are rewritten by the next level
+    }
+    return __uint_as_float(prefix);
+}
+
 __global__ void __launch_bounds__(1024) sample_kernel(const SampleParams p)
 {
     __shared__ float red[16];
     __shared__ int pick;
+    __shared__ unsigned long long hist[kMassBins], wtot[16], ctl[2];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = blockIdx.x;
     int64_t per = ((p.vocab + 15) / 16 + 255) / 256 * 256;   // whole chunks per wavefront
@@ -185,19 +263,11 @@ __global__ void __launch_bounds__(1024) sample_kernel(const SampleParams p)
     w.lane = lane;
     w.vec = (p.vocab % 4 == 0) && ((reinterpret_cast<uintptr_t>(p.probs) & 15u) == 0);
 
-    // pool mass for a threshold: sum of the probabilities >= tau
-    auto mass_at = [&](float tau) {
-        float s = 0.f;
-        w.for_each_chunk([&](int64_t, int64_t, const float (&v)[4]) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) s += (v[e] >= tau) ? v[e] : 0.f;
-        });
-        return block_sum16(wave_sum(s), red, wave, lane);
-    };
-
     // ---- threshold of the pool -------------------------------------------------------------------
     float tau = 0.f;
-    if (p.method != kSampleFull) {
+    if (p.method == kSampleTopP) {
+        tau = top_p_threshold(w, p.param, hist, wtot, ctl, tid);
+    } else if (p.method != kSampleFull) {
         float m = 0.f;
         w.for_each_chunk([&](int64_t, int64_t, const float (&v)[4]) { m = fmaxf(fmaxf(m, fmaxf(v[0], v[1])), fmaxf(v[2], v[3])); });
         m = wave_max(m);
@@ -218,16 +288,6 @@ __global__ void __launch_bounds__(1024) sample_kernel(const SampleParams p)
             });
             const float h = -kLn2 * block_sum16(wave_sum(hs), red, wave, lane);
             tau = fminf(p.param, p.param2 * fast_exp2(-h * kLog2e));
-        } else {
-            // top-p: the largest threshold whose pool still holds mass >= param, by bisection on the
-            // bit pattern (probabilities are non-negative floats, so their bits order like their values)
-            uint32_t lo = 0u, hi = __float_as_uint(p_max) + 1u;      // mass(lo) >= param holds for lo = 0 when param <= total
-            while (hi - lo > 1u) {
-                const uint32_t mid = lo + (hi - lo) / 2u;
-                if (mass_at(__uint_as_float(mid)) >= p.param) lo = mid;
-                else hi = mid;
-            }
-            tau = __uint_as_float(lo);
         }
     }
 

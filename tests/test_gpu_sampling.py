@@ -133,3 +133,27 @@ def test_sampling_frequencies_follow_the_pool_distribution(ts):
         want = np.where(base >= tau, base, 0.0).astype(np.float64)
         want /= want.sum()
         np.testing.assert_allclose(np.bincount(tok, minlength=6) / n, want, rtol=0, atol=2.0 / n)
+
+
+def test_top_p_edge_rows_and_repeatability(ts):
+    """Rows that stress the digit-by-digit threshold search: one dominant token, a long tail of tiny and
+    subnormal probabilities, many equal values around the cut, zeros; the same call twice gives the same
+    tokens, thresholds and masses bit for bit."""
+    import torch
+    rng = np.random.default_rng(7)
+    v = 20000
+    rows = []
+    a = np.full(v, 1e-30, dtype=np.float64); a[123] = 1.0; rows.append(a)                       # dominant token
+    b = rng.random(v) ** 12; b[::3] = 0.0; rows.append(b)                                       # heavy tail + zeros
+    c = np.full(v, 1.0); c[:50] = 40.0; rows.append(c)                                          # plateau: ties at the cut
+    d = np.exp(rng.normal(0, 6.0, v)); d[5] = 1e-44; d[6] = 3e-39; rows.append(d)               # subnormals present
+    e = np.zeros(v); e[[7, 19999]] = 0.5; rows.append(e)                                        # two tokens, rest zero
+    p = np.stack([r / r.sum() for r in rows]).astype(np.float32)
+    pg = torch.from_numpy(p).cuda()
+    u = np.array([0.3, 0.999, 0.5, 0.01, 0.75], dtype=np.float32)
+    for param in (0.05, 0.5, 0.9, 0.999):
+        _check_draws(ts, pg, O.TOP_P, param, u)
+        first = [x.cpu().numpy() for x in ts.sample_tokens(pg, O.TOP_P, param, torch.from_numpy(u).cuda(), want_pool=True)]
+        again = [x.cpu().numpy() for x in ts.sample_tokens(pg, O.TOP_P, param, torch.from_numpy(u).cuda(), want_pool=True)]
+        for x, y in zip(first, again):
+            assert x.tobytes() == y.tobytes()
