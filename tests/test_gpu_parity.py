@@ -97,6 +97,10 @@ def test_topk_special_values(ts):
         np.testing.assert_array_equal(_np(got), oracle.topk_chunks(s, n_sink, k))
     s = np.full((2, 70), 0.25, dtype=np.float32)
     np.testing.assert_array_equal(_np(ts.topk_chunks(torch.from_numpy(s).cuda(), 1, 40)), oracle.topk_chunks(s, 1, 40))
+    # all scores equal over more chunks than one index digit covers: the cut is decided by the index alone
+    for n, k in ((5000, 100), (5000, 3000), (70000, 2049)):
+        s = np.full((2, n), -1.5, dtype=np.float32)
+        np.testing.assert_array_equal(_np(ts.topk_chunks(torch.from_numpy(s).cuda(), 2, k)), oracle.topk_chunks(s, 2, k))
 
 
 def test_scores_then_topk_pipeline(ts):
