@@ -178,8 +178,24 @@ def main():
     def sweep(fn):
         return lambda: [fn(x) for x in layers]
     reps = max(2, args.steps // 4)
-    parts = {name: timed(sweep(fn), reps) * 1e3 / n_layers
+
+    def spread(fn, n_sweeps):
+        """us per layer of fn, each sweep over the layers timed on its own: mean, median, p10, p90."""
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_sweeps + 1)]
+        torch.cuda.synchronize()
+        evs[0].record()
+        for i in range(n_sweeps):
+            for x in layers:
+                fn(x)
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        us = sorted(evs[i].elapsed_time(evs[i + 1]) * 1e3 / n_layers for i in range(n_sweeps))
+        pick = lambda q: us[min(len(us) - 1, int(round(q * (len(us) - 1))))]
+        return {"mean": sum(us) / len(us), "median": pick(0.5), "p10": pick(0.1), "p90": pick(0.9)}
+
+    stats = {name: spread(fn, max(reps, 10))
              for name, fn in (("scores", do_scores), ("topk", do_topk), ("partial", do_partial), ("verify", do_verify))}
+    parts = {name: st["mean"] for name, st in stats.items()}
 
     # cache-maintenance calls around the path (not part of `value`): incremental key sums make
     # the scoring pass read n_chunks*128 floats instead of every key
@@ -232,6 +248,16 @@ def main():
         kern_us = timed(sweep(do_verify), max(1, args.kernel_loops)) * 1e3 / n_layers
     finally:
         ts.tune_set("verify_stage", 0)
+    # what plain reading of the same cache buffers sustains (nothing but loads): the practical ceiling
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    probe_bytes = 0
+    def do_probe(x):
+        ts.stream_read_probe(x["k"], sink)
+        ts.stream_read_probe(x["v"], sink)
+    if all(x["k"].is_contiguous() and x["v"].is_contiguous() for x in layers):
+        probe_bytes = 2 * layers[0]["k"].numel() * 2
+        timed(sweep(do_probe), 1)
+        probe_us = timed(sweep(do_probe), max(1, args.kernel_loops)) * 1e3 / n_layers
     alg_bytes = (hkv * n * cfg.head_dim * 2 * 2 + t * hkv * cfg.head_dim * 2 * 2 + t * hq * cfg.head_dim * 2
                  + t * hq * cfg.head_dim * 4)
     achieved = alg_bytes / (kern_us * 1e-6) / 1e9
@@ -253,6 +279,7 @@ def main():
             cfg.name, hq, hkv, n, cfg.chunk, cfg.k, cfg.n_sink, t, n_layers), "config_index": args.config,
             "layers": n_layers, "n_tokens": n, "launch": "hip graph replay" if args.graph else "eager"},
         "breakdown_us_per_layer": {k: round(v, 3) for k, v in parts.items()},
+        "breakdown_spread_us_per_layer": {k: {q: round(v, 3) for q, v in st.items() if q != "mean"} for k, st in stats.items()},
         "verify_plus_partial_us_per_layer": round(parts["verify"] + parts["partial"], 3),
         "cache_maintenance_us_per_layer": {k: round(v, 3) for k, v in maint.items()},
         "sampling_us_per_step": dict({k: round(v, 3) for k, v in sampling.items()}, rows=t, vocab=vocab, window=1024,
@@ -264,6 +291,12 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": measured_traffic(cfg.name) if n == cfg.n_tokens else None,
                      "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": round(kern_us, 3)},
+        "stream_read_ceiling": ({"GBps": round(probe_bytes / (probe_us * 1e-6) / 1e9, 1), "bytes_per_layer": probe_bytes,
+                                 "us_per_layer": round(probe_us, 3),
+                                 "frac_of_peak": round(probe_bytes / (probe_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                                 "roofline_kernel_frac_of_ceiling": round(achieved / (probe_bytes / (probe_us * 1e-6) / 1e9), 4),
+                                 "what": "a kernel of nothing but 128-bit loads over the same K and V buffers, same rotation"}
+                                if probe_bytes else None),
         "roofline_mfma": {"bound": "mfma", "achieved": round(alg_flops / (kern_us * 1e-6) / 1e12, 2), "peak": 2500.0,
                           "unit": "TFLOP/s", "frac": round(alg_flops / (kern_us * 1e-6) / 2.5e15, 4),
                           "algorithmic_flops_per_launch": alg_flops, "flops_per_byte": round(alg_flops / alg_bytes, 1)},

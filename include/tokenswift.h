@@ -281,6 +281,17 @@ int ts_sample_tokens(const float *probs, int n_rows, int64_t vocab, int method, 
  */
 int ts_tune_set(const char *name, int value);
 
+/*
+ * Measurement utility (no passage of the paper): enqueues a kernel that reads `bytes` bytes at
+ * `src` (device, 16-byte aligned, bytes a multiple of 16) exactly once with 128-bit loads and
+ * does nothing else.  Timed over the cache buffers, it gives the read rate the memory system
+ * sustains, the practical ceiling for the bandwidth-bound passes.  `sink` (device, 4 bytes,
+ * caller-owned) is written only if the buffer's words fold to one particular value; its content
+ * carries no meaning.  Returns TS_ERR_NULL, TS_ERR_SHAPE (size or alignment), TS_ERR_UNSUPPORTED
+ * (more than 2^42 bytes), TS_ERR_HIP, else TS_OK.  Asynchronous on `stream`.
+ */
+int ts_stream_read_probe(const void *src, size_t bytes, uint32_t *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -75,7 +75,8 @@ def load_library():
     lib.ts_sample_tokens.argtypes = [vp, ci, i64, ci, cf, cf, vp, vp, vp, vp, vp]
     lib.ts_penalized_probs.restype = ci
     lib.ts_sample_tokens.restype = ci
-    for name in ("ts_tune_set", "ts_chunk_scores", "ts_topk_chunks", "ts_partial_kv_attn",
+    lib.ts_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    for name in ("ts_stream_read_probe", "ts_tune_set", "ts_chunk_scores", "ts_topk_chunks", "ts_partial_kv_attn",
                  "ts_tree_verify_attn", "ts_append_accepted", "ts_refresh_due", "ts_chunk_list_admit",
                  "ts_gather_chunks", "ts_chunk_key_sums", "ts_chunk_scores_from_sums"):
         getattr(lib, name).restype = ci
@@ -110,6 +111,14 @@ def version() -> int:
 
 def tune_set(name: str, value: int) -> None:
     _check(load_library().ts_tune_set(name.encode(), int(value)), "ts_tune_set")
+
+
+def stream_read_probe(buf: torch.Tensor, sink: torch.Tensor) -> None:
+    """Reads the contiguous tensor `buf` once (measurement utility); `sink`: a 4-byte device tensor."""
+    if not buf.is_contiguous():
+        raise ValueError("buf must be contiguous")
+    _check(load_library().ts_stream_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), _stream()),
+           "ts_stream_read_probe")
 
 
 def workspace_bytes(op: int, n_q_heads: int, n_kv_heads: int, n_tokens: int, n_tree: int = 0,

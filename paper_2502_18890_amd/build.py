@@ -14,7 +14,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libtokenswift_hip.so")
 SOURCES = ["ts_api.hip", "verify_dma_kernel.hip", "verify_wide_kernel.hip", "partial_kernel.hip", "combine_kernel.hip",
-           "scores_kernel.hip", "topk_kernel.hip", "cache_kernels.hip", "sampling_kernels.hip"]
+           "scores_kernel.hip", "topk_kernel.hip", "cache_kernels.hip", "sampling_kernels.hip", "stream_read_kernel.hip"]
 # packed-fp32 instructions are switched off for all device code
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -46,8 +46,8 @@ __global__ void __launch_bounds__(256) gather_kernel(const GatherParams p)
     u32x4 kr = {0u, 0u, 0u, 0u}, vr = {0u, 0u, 0u, 0u};
     if (valid) {
         const int64_t off = (int64_t)h * p.stride_head + t * p.stride_token + c * 8;
-        kr = *reinterpret_cast<const u32x4 *>(p.k + off);
-        vr = *reinterpret_cast<const u32x4 *>(p.v + off);
+        kr = load_stream(p.k + off);
+        vr = load_stream(p.v + off);
     }
     const int64_t o = ((int64_t)h * p.n_sel * p.chunk_size + out_row) * kHeadDim + c * 8;
     *reinterpret_cast<u32x4 *>(p.k_out + o) = kr;
@@ -77,7 +77,7 @@ __global__ void __launch_bounds__(256) ksum_kernel(const KsumParams p)
         for (int i = 0; i < 16; ++i) {
             const int64_t t = t0 + i * 4 + r;
             u32x4 z = {0u, 0u, 0u, 0u};
-            raw[i] = (t < t_end) ? *reinterpret_cast<const u32x4 *>(kbase + t * p.stride_token) : z;
+            raw[i] = (t < t_end) ? load_stream(kbase + t * p.stride_token) : z;
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i)

@@ -64,13 +64,13 @@ __global__ void __launch_bounds__(256) partial_kernel(const PartialParams p)
     for (int kk = 0; kk < kSegKeys; ++kk) {
         const int64_t t = t_begin + kk;
         u32x4 z = {0u, 0u, 0u, 0u};
-        kraw[kk] = (t < t_end) ? *reinterpret_cast<const u32x4 *>(kbase + t * p.stride_token) : z;
+        kraw[kk] = (t < t_end) ? load_stream(kbase + t * p.stride_token) : z;
     }
 #pragma unroll
     for (int kk = 0; kk < kSegKeys; ++kk) {
         const int64_t t = t_begin + kk;
         u32x4 z = {0u, 0u, 0u, 0u};
-        vraw[kk] = (t < t_end) ? *reinterpret_cast<const u32x4 *>(vbase + t * p.stride_token) : z;
+        vraw[kk] = (t < t_end) ? load_stream(vbase + t * p.stride_token) : z;
     }
     float qf[G][8];
 #pragma unroll

@@ -46,7 +46,7 @@ __global__ void __launch_bounds__(256) scores_kernel(const ScoresParams p)
         for (int i = 0; i < 16; ++i) {
             const int64_t t = t0 + i * 4 + r;
             u32x4 z = {0u, 0u, 0u, 0u};
-            raw[i] = (t < t_end) ? *reinterpret_cast<const u32x4 *>(kbase + t * p.stride_token) : z;
+            raw[i] = (t < t_end) ? load_stream(kbase + t * p.stride_token) : z;
         }
 #pragma unroll
         for (int i = 0; i < 16; ++i)

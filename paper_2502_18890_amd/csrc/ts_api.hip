@@ -557,4 +557,12 @@ int ts_sample_tokens(const float *probs, int n_rows, int64_t vocab, int method, 
     return ts::launch_sample(p, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
+int ts_stream_read_probe(const void *src, size_t bytes, uint32_t *sink, void *stream)
+{
+    if (!src || !sink) return TS_ERR_NULL;
+    if (bytes < 16 || bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(src) & 15u) != 0) return TS_ERR_SHAPE;
+    if (bytes / 16 / 2048 >= 0x7fffffffULL) return TS_ERR_UNSUPPORTED;
+    return ts::launch_stream_read(src, (int64_t)(bytes / 16), sink, static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
 }  // extern "C"

@@ -192,4 +192,7 @@ struct SampleParams {
 };
 hipError_t launch_sample(const SampleParams &p, hipStream_t stream);
 
+// ---- streaming-read probe (stream_read_kernel.hip) ----------------------------------------------
+hipError_t launch_stream_read(const void *src, int64_t n_vec, uint32_t *sink, hipStream_t stream);
+
 }  // namespace ts

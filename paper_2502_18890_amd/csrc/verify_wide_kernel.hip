@@ -206,9 +206,9 @@ verify_wide_kernel(const VerifyParams p)
                 const int ii = wave * LPW + i;                       // wave-uniform
                 const uint32_t go = goff[i];
                 if (ii < 8)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void_ptr)(stage + ii * 1024), 16, go, 0, 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void_ptr)(stage + ii * 1024), 16, go, 0, 0, kCachePolicyStream);
                 else
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void_ptr)(stage + kVHalf + (ii - 8) * 1024), 16, go, 0, 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void_ptr)(stage + kVHalf + (ii - 8) * 1024), 16, go, 0, 0, kCachePolicyStream);
             }
             kfill += tile_elems;     // past the range the descriptor covers 0 bytes, so the base is never dereferenced
             vfill += tile_elems;

@@ -32,7 +32,7 @@ def test_library_exports_every_declared_function(lib):
     names = sorted(set(re.findall(r"\b(ts_[a-z_]+)\s*\(", text)))
     assert names == ["ts_append_accepted", "ts_chunk_key_sums", "ts_chunk_list_admit", "ts_chunk_scores",
                      "ts_chunk_scores_from_sums", "ts_gather_chunks", "ts_partial_kv_attn", "ts_penalized_probs",
-                     "ts_refresh_due", "ts_sample_tokens", "ts_sampling_workspace_bytes", "ts_strerror",
+                     "ts_refresh_due", "ts_sample_tokens", "ts_sampling_workspace_bytes", "ts_stream_read_probe", "ts_strerror",
                      "ts_topk_chunks", "ts_tree_verify_attn", "ts_tune_set", "ts_version", "ts_workspace_bytes"]
     for n in names:
         assert hasattr(lib, n), n
@@ -139,6 +139,16 @@ def test_tune_set(lib):
     assert lib.ts_tune_set(b"no_such_knob", 1) == TS_ERR_UNSUPPORTED
     assert lib.ts_tune_set(b"verify_splits", -1) == TS_ERR_UNSUPPORTED
     assert lib.ts_tune_set(None, 1) == TS_ERR_UNSUPPORTED
+
+
+def test_stream_read_probe_rejects_bad_arguments(lib):
+    p = ctypes.c_void_p(4096)
+    assert lib.ts_stream_read_probe(None, 1024, p, None) == TS_ERR_NULL
+    assert lib.ts_stream_read_probe(p, 1024, None, None) == TS_ERR_NULL
+    assert lib.ts_stream_read_probe(p, 0, p, None) == TS_ERR_SHAPE
+    assert lib.ts_stream_read_probe(p, 1000, p, None) == TS_ERR_SHAPE              # not a multiple of 16
+    assert lib.ts_stream_read_probe(ctypes.c_void_p(4100), 1024, p, None) == TS_ERR_SHAPE   # misaligned
+    assert lib.ts_stream_read_probe(p, 1 << 60, p, None) == TS_ERR_UNSUPPORTED
 
 
 def test_cache_maintenance_calls_reject_bad_arguments(lib, binding):

@@ -135,3 +135,19 @@ def test_key_sums_token_major_layout(ts):
     k_tm = rand_bits(rng, n, hkv, D)
     ks = ts.chunk_key_sums(dev(k_tm).transpose(0, 1), 64)
     assert_close(ks.cpu().numpy(), C.chunk_key_sums(np.ascontiguousarray(k_tm.transpose(1, 0, 2)), 64), "key sums token-major")
+
+
+def test_stream_read_probe_reads_every_vector(ts):
+    """The measurement probe folds what it reads into a word that it stores only when the fold hits one
+    value: a buffer of zeros leaves the sink alone, and planting that value anywhere (first vector,
+    a middle one, the last one of a ragged tail) makes the owning thread store it."""
+    import torch
+    n_words = (3 * 32768 + 5 * 16) // 4            # three whole workgroup pieces and a ragged tail
+    for where in (None, 0, n_words // 2 + 1, n_words - 1):
+        buf = torch.zeros(n_words, dtype=torch.int32, device="cuda")
+        if where is not None:
+            buf[where] = 0x5CA1AB1E
+        sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ts.stream_read_probe(buf, sink)
+        torch.cuda.synchronize()
+        assert int(sink.item()) == (0 if where is None else 0x5CA1AB1E)
