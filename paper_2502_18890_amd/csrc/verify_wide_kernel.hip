@@ -169,6 +169,8 @@ verify_wide_kernel(const VerifyParams p)
     }
 
     float m_run[NRB], l_run[NRB];
+    float m_limit[NRB];   // (m_run + kRescaleSlack) in raw logit units: the largest raw logit the reference still covers
+    const float inv_scale_log2 = 1.0f / p.scale_log2;
     f32x16 oacc[NRB][4];
     // ---- HBM -> LDS -------------------------------------------------------------------------
     // Load instruction ii (0..15) of a tile fills LDS block ii: K rows 4ii..4ii+3 for ii < 8,
@@ -250,6 +252,7 @@ verify_wide_kernel(const VerifyParams p)
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
             m_run[rb] = kNegBig;
+            m_limit[rb] = kNegBig;   // any finite logit moves the reference
             l_run[rb] = 0.f;
 #pragma unroll
             for (int cb = 0; cb < 4; ++cb)
@@ -370,12 +373,14 @@ verify_wide_kernel(const VerifyParams p)
                 }
         }
 
-        // Row maxima (raw logits; scale > 0 commutes with max).  Element e of sacc is key
-        // hh*4 + 8*(e/4) + e%4 of the tile, for query row n32.  m_run is a reference point, not
-        // necessarily the exact running maximum: the accumulators are rescaled only when a tile's
-        // maximum exceeds it by more than kRescaleSlack, so the weights stay <= 2^kRescaleSlack and
-        // the (rare) rescale leaves the common path.
-        float m_tile[L > 0 ? L : 1];
+        // m_run is a reference point, not necessarily the exact running maximum: the accumulators are
+        // rescaled only when a logit exceeds it by more than kRescaleSlack, so the weights stay
+        // <= 2^kRescaleSlack and the (rare) rescale leaves the common path.  The common path only
+        // compares each lane's largest raw logit (scale > 0 commutes with max) with m_limit, the same
+        // bound in raw units; the row maximum across the two lanes of a row, the new reference and the
+        // rescaling are the rare path's.  Element e of sacc is key hh*4 + 8*(e/4) + e%4 of the tile, for
+        // query row n32.
+        float mloc[L > 0 ? L : 1];
         bool moved = false;
 #pragma unroll
         for (int rb = 0; rb < L; ++rb) {
@@ -394,16 +399,17 @@ verify_wide_kernel(const VerifyParams p)
                 for (int e = 0; e < 16; ++e)
                     if (!((vm >> (8 * (e >> 2) + (e & 3))) & 1u)) sacc[rb][e] = -INFINITY;
             }
-            float mloc = sacc[rb][0];
+            // three-input maxima: eight instructions for sixteen values
+            float m = fmaxf(fmaxf(sacc[rb][0], sacc[rb][1]), sacc[rb][2]);
 #pragma unroll
-            for (int e = 1; e < 16; ++e) mloc = fmaxf(mloc, sacc[rb][e]);
-            m_tile[rb] = swap32_max(mloc) * p.scale_log2;
-            moved |= (m_tile[rb] > m_run[rb] + kRescaleSlack);
+            for (int e = 3; e < 15; e += 2) m = fmaxf(fmaxf(m, sacc[rb][e]), sacc[rb][e + 1]);
+            mloc[rb] = fmaxf(m, sacc[rb][15]);
+            moved |= mloc[rb] > m_limit[rb];
         }
         if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {   // some row of this wavefront outgrew its reference
 #pragma unroll
             for (int rb = 0; rb < L; ++rb) {
-                const float m_new = fmaxf(m_run[rb], m_tile[rb]);
+                const float m_new = fmaxf(m_run[rb], swap32_max(mloc[rb]) * p.scale_log2);   // both lanes of a row agree on it
                 const float alpha = fast_exp2(m_run[rb] - m_new);
                 l_run[rb] *= alpha;
 #pragma unroll
@@ -411,12 +417,13 @@ verify_wide_kernel(const VerifyParams p)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) oacc[rb][cb][e] *= alpha;
                 m_run[rb] = m_new;
+                m_limit[rb] = (m_new + kRescaleSlack) * inv_scale_log2;
             }
         }
 
         // fp16 weights carry 11 bits.  That is enough where a row's weight is spread over many keys
         // (independent rounding errors of 2^-12 each), not where a few keys hold it: a tile in
-        // which some row's largest weight reaches kResidualShare of what that row has accumulated
+        // which some lane's largest weight reaches kResidualShare of what that lane has accumulated
         // so far also multiplies the rounding residuals (fp16 again, 22 bits in all).  That second
         // product sits in a loop that runs zero or one times rather than in a branch:
         // accumulators updated inside an if get copied at the join, loop-carried ones stay put.
@@ -425,7 +432,7 @@ verify_wide_kernel(const VerifyParams p)
             bool concentrated = false;
 #pragma unroll
             for (int rb = 0; rb < L; ++rb)
-                concentrated |= fast_exp2(m_tile[rb] - m_run[rb] + kHalfShift) >= kResidualShare * l_run[rb];
+                concentrated |= fast_exp2(fmaf(mloc[rb], p.scale_log2, kHalfShift - m_run[rb])) >= kResidualShare * l_run[rb];
             n_trips = __builtin_amdgcn_ballot_w64(concentrated) != 0ull ? 2 : 1;
         }
 
