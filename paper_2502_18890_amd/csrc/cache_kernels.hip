@@ -91,8 +91,8 @@ __global__ void __launch_bounds__(256) ksum_kernel(const KsumParams p)
     for (int x = 0; x < 8; ++x) ksum[x] = xrow_sum(ksum[x]);
     if (r == 0) {
         float *dst = p.ksum + (int64_t)h * p.ksum_stride_head + chunk * kHeadDim + c * 8;
-        *reinterpret_cast<f32x4 *>(dst) = f32x4{ksum[0], ksum[1], ksum[2], ksum[3]};
-        *reinterpret_cast<f32x4 *>(dst + 4) = f32x4{ksum[4], ksum[5], ksum[6], ksum[7]};
+        __builtin_nontemporal_store(f32x4{ksum[0], ksum[1], ksum[2], ksum[3]}, reinterpret_cast<f32x4 *>(dst));
+        __builtin_nontemporal_store(f32x4{ksum[4], ksum[5], ksum[6], ksum[7]}, reinterpret_cast<f32x4 *>(dst + 4));
     }
 }
 
