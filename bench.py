@@ -2,10 +2,13 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
 
-One step = one pass of the whole path (chunk scores -> top-k -> partial-KV attention -> tree
-verification) over every layer's own cache of the workload; caches are resident in HBM before
-the timed region and each layer has its own, so every launch reads cold data.  Prints one
-JSON line: `value` is microseconds per layer-step (all four calls, one layer's cache);
+One step = one pass of the whole path over every layer's own cache of the workload, in the
+order of the method's loop: tree verification over the full cache, which also leaves the chunk
+scores (the query-key products of the tree's first token are the scores' terms, so the keys are
+read once for both), top-k, partial-KV attention.  `--four-pass` times the step with the scores
+as a pass of their own instead; either way the other step's time is reported beside it.  Caches
+are resident in HBM before the timed region and each layer has its own, so every launch reads
+cold data.  Prints one JSON line: `value` is microseconds per layer-step (one layer's cache);
 `roofline` is the split kernel of the verification pass, its algorithmic bytes (K and V of the
 cache and tree, queries, outputs) over its average duration from HIP events, against 8 TB/s;
 `roofline_mfma` the same kernel's algorithmic flops; `cpu_baseline` the fp64 oracle timed on the
@@ -49,6 +52,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layer caches (0 = the config's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-loops", type=int, default=2, help="extra sweeps of the verify kernel alone for the roofline figure")
+    ap.add_argument("--four-pass", action="store_true",
+                    help="time the step with the chunk scores as a pass of their own (ts_chunk_scores) instead of "
+                         "leaving them to the verification pass (ts_tree_verify_attn_scored)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one whole step (all layers) in a HIP graph and time its replays instead of eager launches")
     ap.add_argument("--hold", type=float, default=0.0,
@@ -108,6 +114,7 @@ def main():
     layers = [S.make_layer_torch(cfg, l, dev) for l in range(n_layers)]
     hq, hkv, n, t = cfg.n_q_heads, cfg.n_kv_heads, cfg.n_tokens, cfg.n_tree
     ws_v = torch.empty(ts.workspace_bytes(ts.OP_TREE_VERIFY, hq, hkv, n, t), dtype=torch.uint8, device=dev)
+    ws_vs = torch.empty(ts.workspace_bytes(ts.OP_TREE_VERIFY_SCORED, hq, hkv, n, t), dtype=torch.uint8, device=dev)
     ws_p = torch.empty(ts.workspace_bytes(ts.OP_PARTIAL_ATTN, hq, hkv, n, 0, cfg.n_sel, cfg.chunk), dtype=torch.uint8, device=dev)
     scores = torch.empty(hkv, cfg.n_chunks, dtype=torch.float32, device=dev)
     idx = torch.empty(hkv, cfg.n_sel, dtype=torch.int32, device=dev)
@@ -128,12 +135,28 @@ def main():
         ts.tree_verify_attn(x["q_tree"], x["k"], x["v"], x["k_tree"], x["v_tree"], x["parent"], cfg.scale,
                             out=out_v, workspace=ws_v)
 
-    def step():
+    def do_verify_scored(x):
+        # the verification pass also leaves the chunk scores for the query of tree node 0 (= x["q"] in these inputs)
+        ts.tree_verify_attn(x["q_tree"], x["k"], x["v"], x["k_tree"], x["v_tree"], x["parent"], cfg.scale,
+                            out=out_v, workspace=ws_vs, score_chunk=cfg.chunk, scores=scores)
+
+    def step_four_pass():
         for x in layers:
             do_scores(x)
             do_topk(x)
             do_partial(x)
             do_verify(x)
+
+    def step_scored():
+        # the order of Alg. 1: verification over the full cache (whose query-key products give the scores),
+        # rebuild of the partial cache's chunk list, drafting pass over it
+        for x in layers:
+            do_verify_scored(x)
+            do_topk(x)
+            do_partial(x)
+
+    step = step_four_pass if args.four_pass else step_scored
+    do_verify_timed = do_verify if args.four_pass else do_verify_scored
 
     def timed(fn, reps):
         """ms per call of fn over reps calls, HIP events on the current stream."""
@@ -148,7 +171,15 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    (step_scored if args.four_pass else step_four_pass)()   # the other step, timed after the K steps for comparison
     torch.cuda.synchronize()
+    # both ways of getting the scores select the same chunks (same query, same keys; sums in another order)
+    x0 = layers[0]
+    do_scores(x0); do_topk(x0)
+    idx_a = idx.clone()
+    do_verify_scored(x0); do_topk(x0)
+    same_sets = sum(len(set(a.tolist()) & set(b.tolist())) for a, b in zip(idx_a.cpu(), idx.cpu())) / float(idx.numel())
+    assert same_sets > 0.98, "scores from the verification pass select other chunks than the scoring pass (%.3f)" % same_sets
     if args.hold > 0:
         t_start, calls = time.time(), 0
         while time.time() - t_start < args.hold:
@@ -173,6 +204,8 @@ def main():
     wall0 = time.perf_counter()
     ms_per_step = timed(run_step, args.steps)
     wall = time.perf_counter() - wall0
+    other_step = step_scored if args.four_pass else step_four_pass
+    ms_other = timed(other_step, max(2, args.steps // 4))
 
     # per-function breakdown (each swept over all layers, same rotation)
     def sweep(fn):
@@ -194,7 +227,8 @@ def main():
         return {"mean": sum(us) / len(us), "median": pick(0.5), "p10": pick(0.1), "p90": pick(0.9)}
 
     stats = {name: spread(fn, max(reps, 10))
-             for name, fn in (("scores", do_scores), ("topk", do_topk), ("partial", do_partial), ("verify", do_verify))}
+             for name, fn in (("scores", do_scores), ("topk", do_topk), ("partial", do_partial), ("verify", do_verify),
+                              ("verify_scored", do_verify_scored))}
     parts = {name: st["mean"] for name, st in stats.items()}
 
     # cache-maintenance calls around the path (not part of `value`): incremental key sums make
@@ -244,8 +278,8 @@ def main():
     # the dominant kernel alone (split kernel of the verification pass), for the roofline
     ts.tune_set("verify_stage", 1)
     try:
-        timed(sweep(do_verify), 1)
-        kern_us = timed(sweep(do_verify), max(1, args.kernel_loops)) * 1e3 / n_layers
+        timed(sweep(do_verify_timed), 1)
+        kern_us = timed(sweep(do_verify_timed), max(1, args.kernel_loops)) * 1e3 / n_layers
     finally:
         ts.tune_set("verify_stage", 0)
     # what plain reading of the same cache buffers sustains (nothing but loads): the practical ceiling
@@ -278,6 +312,10 @@ def main():
         "config": {"workload": "%s: %d q heads / %d kv heads, d=128, N=%d cached tokens, chunk %d, top-k %d+%d chunks, tree %d nodes, %d layer caches, batch 1" % (
             cfg.name, hq, hkv, n, cfg.chunk, cfg.k, cfg.n_sink, t, n_layers), "config_index": args.config,
             "layers": n_layers, "n_tokens": n, "launch": "hip graph replay" if args.graph else "eager"},
+        "step": ("four passes: ts_chunk_scores, ts_topk_chunks, ts_partial_kv_attn, ts_tree_verify_attn" if args.four_pass else
+                 "three passes: ts_tree_verify_attn_scored (verification; its query-key products of tree node 0 also give the "
+                 "chunk scores, same values as ts_chunk_scores for that query), ts_topk_chunks, ts_partial_kv_attn"),
+        "other_step_us_per_layer": {("scores_left_to_verification" if args.four_pass else "four_passes"): round(ms_other * 1e3 / n_layers, 3)},
         "breakdown_us_per_layer": {k: round(v, 3) for k, v in parts.items()},
         "breakdown_spread_us_per_layer": {k: {q: round(v, 3) for q, v in st.items() if q != "mean"} for k, st in stats.items()},
         "verify_plus_partial_us_per_layer": round(parts["verify"] + parts["partial"], 3),

@@ -64,7 +64,7 @@ typedef struct {
     int64_t stride_token;   /* elements; multiple of 8, >= head_dim, <= TS_MAX_STRIDE_TOKEN */
 } ts_kv_view;
 
-enum { TS_OP_PARTIAL_ATTN = 1, TS_OP_TREE_VERIFY = 2 };
+enum { TS_OP_PARTIAL_ATTN = 1, TS_OP_TREE_VERIFY = 2, TS_OP_TREE_VERIFY_SCORED = 3 };
 
 /*
  * All calls enqueue kernels on the caller's stream and return; none allocates, synchronises or
@@ -81,7 +81,7 @@ int ts_version(void);
 /*
  * Bytes of device workspace that the split-K attention calls need for the given shape
  * (0 on invalid arguments).  op is TS_OP_PARTIAL_ATTN (n_sel, chunk_size used; n_tree ignored)
- * or TS_OP_TREE_VERIFY (n_tree used; n_sel, chunk_size ignored).  The workspace holds the
+ * or TS_OP_TREE_VERIFY / TS_OP_TREE_VERIFY_SCORED (n_tree used; n_sel, chunk_size ignored).  The workspace holds the
  * per-split softmax partials (running max, sum of exponentials, unnormalised output) that a
  * second kernel merges; its contents are scratch and need no initialisation.
  */
@@ -158,6 +158,24 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
                         const void *k_tree, const void *v_tree, const int32_t *parent,
                         int n_tree, float scale, float *out, float *lse, void *workspace,
                         size_t workspace_bytes, void *stream);
+
+/*
+ * The same verification pass, which also leaves the chunk importance scores of the cache (Sec. 3.3:
+ * the scores are recalculated from the query-key products of the forward pass over the full
+ * cache; Eq. 2) for the query of tree node 0, the token the iteration started from:
+ *   scores[h][c] = scale * mean over the tokens t of chunk c of sum_{j in group h} q_tree[0][j] . K[h][t],
+ * i.e. what ts_chunk_scores returns for q = q_tree[0], at no extra pass over the keys: the rows of node 0
+ * hold these products anyway.
+ *   scores      fp32 [n_kv_heads][ceil(N / chunk_size)]  (written; valid when the stream reaches the call)
+ *   chunk_size  multiple of 32, 32..1024 (TS_ERR_UNSUPPORTED otherwise)
+ *   workspace   >= ts_workspace_bytes(TS_OP_TREE_VERIFY_SCORED, ...) bytes, 256-byte aligned
+ * kv->n_tokens must be >= 1 (TS_ERR_SHAPE).  Everything else as for ts_tree_verify_attn; out and lse are
+ * the same as that call's.
+ */
+int ts_tree_verify_attn_scored(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
+                               const void *k_tree, const void *v_tree, const int32_t *parent,
+                               int n_tree, float scale, int chunk_size, float *scores, float *out,
+                               float *lse, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------
  * Cache maintenance around the attention calls (Alg. 1: the update of C_full and the eviction

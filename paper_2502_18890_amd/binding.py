@@ -18,6 +18,7 @@ _LIB_PATH = os.environ.get("TOKENSWIFT_LIB", os.path.join(_PKG, "libtokenswift_h
 
 OP_PARTIAL_ATTN = 1
 OP_TREE_VERIFY = 2
+OP_TREE_VERIFY_SCORED = 3
 HEAD_DIM = 128
 
 
@@ -62,6 +63,8 @@ def load_library():
     lib.ts_partial_kv_attn.argtypes = [kvp, vp, ci, vp, ci, ci, cf, vp, vp, vp, ctypes.c_size_t, vp]
     lib.ts_tree_verify_attn.argtypes = [kvp, vp, ci, vp, vp, ctypes.POINTER(ctypes.c_int32), ci, cf,
                                         vp, vp, vp, ctypes.c_size_t, vp]
+    lib.ts_tree_verify_attn_scored.argtypes = [kvp, vp, ci, vp, vp, ctypes.POINTER(ctypes.c_int32), ci, cf, ci, vp,
+                                               vp, vp, vp, ctypes.c_size_t, vp]
     i32p = ctypes.POINTER(ctypes.c_int32)
     lib.ts_append_accepted.argtypes = [kvp, vp, vp, ci, i32p, ci, vp]
     lib.ts_refresh_due.argtypes = [i64, i64, i64, i64]
@@ -77,7 +80,7 @@ def load_library():
     lib.ts_sample_tokens.restype = ci
     lib.ts_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp, vp]
     for name in ("ts_stream_read_probe", "ts_tune_set", "ts_chunk_scores", "ts_topk_chunks", "ts_partial_kv_attn",
-                 "ts_tree_verify_attn", "ts_append_accepted", "ts_refresh_due", "ts_chunk_list_admit",
+                 "ts_tree_verify_attn", "ts_tree_verify_attn_scored", "ts_append_accepted", "ts_refresh_due", "ts_chunk_list_admit",
                  "ts_gather_chunks", "ts_chunk_key_sums", "ts_chunk_scores_from_sums"):
         getattr(lib, name).restype = ci
     _lib = lib
@@ -188,9 +191,13 @@ def partial_kv_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, chunk_idx
 def tree_verify_attn(q_tree: torch.Tensor, k: Optional[torch.Tensor], v: Optional[torch.Tensor],
                      k_tree: torch.Tensor, v_tree: torch.Tensor, parent: Sequence[int], scale: float,
                      out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
-                     workspace: Optional[torch.Tensor] = None, want_lse: bool = False):
+                     workspace: Optional[torch.Tensor] = None, want_lse: bool = False,
+                     score_chunk: int = 0, scores: Optional[torch.Tensor] = None):
     """q_tree [T,Hq,128], k/v [Hkv,N,128] (or None for an empty cache), k_tree/v_tree [T,Hkv,128]
-    bf16, parent host ints [T] -> out fp32 [T,Hq,128] (and lse fp32 [T,Hq])."""
+    bf16, parent host ints [T] -> out fp32 [T,Hq,128] (and lse fp32 [T,Hq]).
+    With score_chunk > 0 the call is ts_tree_verify_attn_scored: the chunk scores of the cache for the
+    query of tree node 0 (fp32 [Hkv, ceil(N/score_chunk)]) are written to `scores` (allocated if None)
+    and returned last."""
     lib = load_library()
     q_tree = q_tree.contiguous()
     k_tree = k_tree.contiguous()
@@ -202,15 +209,27 @@ def tree_verify_attn(q_tree: torch.Tensor, k: Optional[torch.Tensor], v: Optiona
     par = (ctypes.c_int32 * len(parent))(*[int(x) for x in parent])
     if len(parent) != t:
         raise ValueError("parent must have one entry per tree node")
-    nbytes = workspace_bytes(OP_TREE_VERIFY, hq, hkv, n_tokens, t)
+    scored = score_chunk > 0
+    nbytes = workspace_bytes(OP_TREE_VERIFY_SCORED if scored else OP_TREE_VERIFY, hq, hkv, n_tokens, t)
     workspace = _workspace(nbytes, q_tree.device, workspace)
     if out is None:
         out = torch.empty(t, hq, HEAD_DIM, dtype=torch.float32, device=q_tree.device)
     if lse is None and want_lse:
         lse = torch.empty(t, hq, dtype=torch.float32, device=q_tree.device)
+    lse_ptr = lse.data_ptr() if lse is not None else None
+    if scored:
+        n_chunks = (n_tokens + score_chunk - 1) // score_chunk
+        if scores is None:
+            scores = torch.empty(hkv, max(n_chunks, 1), dtype=torch.float32, device=q_tree.device)
+        elif scores.dtype != torch.float32 or not scores.is_contiguous() or scores.numel() < hkv * n_chunks:
+            raise ValueError("scores must be a contiguous fp32 [Hkv, n_chunks] tensor")
+        _check(lib.ts_tree_verify_attn_scored(ctypes.byref(kv), q_tree.data_ptr(), hq, k_tree.data_ptr(), v_tree.data_ptr(),
+                                              par, t, float(scale), int(score_chunk), scores.data_ptr(), out.data_ptr(),
+                                              lse_ptr, workspace.data_ptr(), workspace.numel(), _stream()),
+               "ts_tree_verify_attn_scored")
+        return (out, lse, scores) if lse is not None else (out, scores)
     _check(lib.ts_tree_verify_attn(ctypes.byref(kv), q_tree.data_ptr(), hq, k_tree.data_ptr(), v_tree.data_ptr(),
-                                   par, t, float(scale), out.data_ptr(),
-                                   lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
+                                   par, t, float(scale), out.data_ptr(), lse_ptr, workspace.data_ptr(),
                                    workspace.numel(), _stream()), "ts_tree_verify_attn")
     return (out, lse) if lse is not None else out
 

@@ -16,8 +16,27 @@ __global__ void __launch_bounds__(256) combine_kernel(const CombineParams p)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int row = blockIdx.x * 4 + wave;
     const int h = blockIdx.y;
+    const int row_blocks = (p.n_rows + 3) / 4;
+    if ((int)blockIdx.x >= row_blocks) {
+        // Workgroups behind the row blocks: chunk scores (Eq. 2 with the first tree node's queries) from the
+        // per-tile sums of raw logits that the split kernel left: one chunk per thread.
+        const int64_t c = (int64_t)(blockIdx.x - row_blocks) * 256 + threadIdx.x;
+        if (c >= p.n_chunks) return;
+        const int tiles_per_chunk = p.chunk_size / 32;
+        const int64_t n_tiles = (p.n_tokens + 31) / 32;
+        const float *ts = p.tile_sums + (int64_t)h * p.tile_sums_stride;
+        float s = 0.f;
+        for (int i = 0; i < tiles_per_chunk; ++i) {
+            const int64_t t = c * tiles_per_chunk + i;
+            if (t < n_tiles) s += ts[t];
+        }
+        int64_t count = p.n_tokens - c * p.chunk_size;
+        if (count > p.chunk_size) count = p.chunk_size;
+        p.scores[(int64_t)h * p.n_chunks + c] = p.scale * s / (float)count;
+        return;
+    }
+    const int row = blockIdx.x * 4 + wave;
     if (row >= p.n_rows) return;   // whole wavefront leaves together
 
     const int64_t pitch = p.row_pitch;
@@ -66,7 +85,8 @@ __global__ void __launch_bounds__(256) combine_kernel(const CombineParams p)
 
 hipError_t launch_combine(const CombineParams &p, hipStream_t stream)
 {
-    dim3 grid((p.n_rows + 3) / 4, p.n_kv_heads);
+    const unsigned score_blocks = p.tile_sums ? (unsigned)((p.n_chunks + 255) / 256) : 0u;
+    dim3 grid((p.n_rows + 3) / 4 + score_blocks, p.n_kv_heads);
     hipLaunchKernelGGL(combine_kernel, grid, dim3(256), 0, stream, p);
     return hipGetLastError();
 }

@@ -48,13 +48,14 @@ struct VerifyPlan {
     ts::VerifyShape shape;
     int n_rows, n_rows_pad, n_split;
     int64_t split_len;
-    size_t ml_offset, bytes;
+    size_t ml_offset, tile_offset, bytes;   // tile_offset: per-tile logit sums of the scored variant (0 bytes otherwise)
+    int64_t n_tiles;
 };
 
 // Splits of the cache: as many workgroups as the chip holds at once (so that the grid runs as
 // one resident wave with every CU's latency-hiding slots full), but few enough that the fp32
 // partials (520 B per row and split) stay a small fraction of the K/V bytes (512 B per token).
-bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, VerifyPlan *pl)
+bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, bool scored, VerifyPlan *pl)
 {
     const int group = n_q_heads / n_kv_heads;
     pl->n_rows = group * n_tree;
@@ -79,7 +80,9 @@ bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, Ve
     pl->split_len = split_len;
     const size_t rows_total = (size_t)n_kv_heads * (n_split + 1) * pl->n_rows_pad;
     pl->ml_offset = round_up(rows_total * TS_HEAD_DIM * sizeof(float), 256);
-    pl->bytes = pl->ml_offset + round_up(rows_total * 2 * sizeof(float), 256);
+    pl->tile_offset = pl->ml_offset + round_up(rows_total * 2 * sizeof(float), 256);
+    pl->n_tiles = (n_tokens + 31) / 32;
+    pl->bytes = pl->tile_offset + (scored ? round_up((size_t)n_kv_heads * pl->n_tiles * sizeof(float), 256) : 0);
     return true;
 }
 
@@ -188,10 +191,10 @@ size_t ts_workspace_bytes(int op, int n_q_heads, int n_kv_heads, int64_t n_token
 {
     int group = 0;
     if (check_heads(n_q_heads, n_kv_heads, &group) != TS_OK) return 0;
-    if (op == TS_OP_TREE_VERIFY) {
+    if (op == TS_OP_TREE_VERIFY || op == TS_OP_TREE_VERIFY_SCORED) {
         if (n_tree < 1 || n_tree > TS_MAX_TREE || n_tokens < 0) return 0;
         VerifyPlan pl;
-        if (!plan_verify(n_q_heads, n_kv_heads, n_tokens, n_tree, &pl)) return 0;
+        if (!plan_verify(n_q_heads, n_kv_heads, n_tokens, n_tree, op == TS_OP_TREE_VERIFY_SCORED, &pl)) return 0;
         return pl.bytes;
     }
     if (op == TS_OP_PARTIAL_ATTN) {
@@ -286,7 +289,7 @@ int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
     p.scale_log2 = scale * 1.4426950408889634f;
     if (ts::launch_partial(p, st) != hipSuccess) return TS_ERR_HIP;
 
-    ts::CombineParams c;
+    ts::CombineParams c{};
     c.ws_o = p.ws_o;
     c.ws_ml = p.ws_ml;
     c.out = out;
@@ -300,10 +303,11 @@ int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
     return ts::launch_combine(c, st) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 
-int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
-                        const void *k_tree, const void *v_tree, const int32_t *parent,
-                        int n_tree, float scale, float *out, float *lse, void *workspace,
-                        size_t workspace_bytes, void *stream)
+// ts_tree_verify_attn, and with scores != nullptr ts_tree_verify_attn_scored
+static int verify_call(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
+                       const void *k_tree, const void *v_tree, const int32_t *parent,
+                       int n_tree, float scale, int chunk_size, float *scores, float *out, float *lse,
+                       void *workspace, size_t workspace_bytes, void *stream)
 {
     int rc = check_view(kv, true, true);
     if (rc != TS_OK) return rc;
@@ -316,7 +320,7 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
         if (parent[i] < -1 || parent[i] >= i) return TS_ERR_TREE;
     if (!aligned16(q_tree) || !aligned16(k_tree) || !aligned16(v_tree) || !aligned16(out)) return TS_ERR_ALIGN;
     VerifyPlan pl;
-    if (!plan_verify(n_q_heads, kv->n_kv_heads, kv->n_tokens, n_tree, &pl)) return TS_ERR_UNSUPPORTED;
+    if (!plan_verify(n_q_heads, kv->n_kv_heads, kv->n_tokens, n_tree, scores != nullptr, &pl)) return TS_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < pl.bytes || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return TS_ERR_WORKSPACE;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -328,6 +332,8 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
     p.v_tree = static_cast<const uint16_t *>(v_tree);
     p.ws_o = reinterpret_cast<float *>(workspace);
     p.ws_ml = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.ml_offset);
+    p.tile_sums = scores ? reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.tile_offset) : nullptr;
+    p.tile_sums_stride = pl.n_tiles;
     p.stride_head = kv->stride_head;
     p.stride_token = kv->stride_token;
     p.n_tokens = kv->n_tokens;
@@ -357,7 +363,7 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
     }
     if (g_tune.verify_stage == 1) return TS_OK;
 
-    ts::CombineParams c;
+    ts::CombineParams c{};
     c.ws_o = p.ws_o;
     c.ws_ml = p.ws_ml;
     c.out = out;
@@ -368,7 +374,35 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
     c.n_part = pl.n_split + 1;
     c.n_rows = pl.n_rows;
     c.row_pitch = pl.n_rows_pad;
+    c.tile_sums = p.tile_sums;
+    c.scores = scores;
+    c.tile_sums_stride = pl.n_tiles;
+    c.n_tokens = kv->n_tokens;
+    c.chunk_size = chunk_size;
+    c.n_chunks = scores ? (kv->n_tokens + chunk_size - 1) / chunk_size : 0;
+    c.scale = scale;
     return ts::launch_combine(c, st) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
+                        const void *k_tree, const void *v_tree, const int32_t *parent,
+                        int n_tree, float scale, float *out, float *lse, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    return verify_call(kv, q_tree, n_q_heads, k_tree, v_tree, parent, n_tree, scale, 0, nullptr, out, lse, workspace,
+                       workspace_bytes, stream);
+}
+
+int ts_tree_verify_attn_scored(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
+                               const void *k_tree, const void *v_tree, const int32_t *parent,
+                               int n_tree, float scale, int chunk_size, float *scores, float *out,
+                               float *lse, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!scores) return TS_ERR_NULL;
+    if (kv && kv->n_tokens < 1) return TS_ERR_SHAPE;                         // nothing to score
+    if (chunk_size < 32 || chunk_size > 1024 || chunk_size % 32 != 0) return TS_ERR_UNSUPPORTED;   // whole 32-key tiles
+    return verify_call(kv, q_tree, n_q_heads, k_tree, v_tree, parent, n_tree, scale, chunk_size, scores, out, lse, workspace,
+                       workspace_bytes, stream);
 }
 
 int ts_append_accepted(const ts_kv_view *kv, const void *k_tree, const void *v_tree, int n_tree,

@@ -30,6 +30,9 @@ struct VerifyParams {
     const uint16_t *v_tree;
     float *ws_o;              // [n_kv_heads][n_split+1][n_rows_pad][128]
     float *ws_ml;             // [n_kv_heads][n_split+1][n_rows_pad][2]  (max in exp2 domain, sum)
+    float *tile_sums;         // nullptr, or [n_kv_heads][tile_sums_stride]: per 32-key tile of the cache, the sum over its
+                              // valid keys of the raw logits q.k of the first tree node's query heads of the group
+    int64_t tile_sums_stride;
     int64_t stride_head, stride_token;
     int64_t n_tokens;
     int64_t split_len;        // cached tokens per split, multiple of 32
@@ -101,6 +104,12 @@ struct CombineParams {
     float *lse;               // [n_nodes][n_q_heads] or nullptr
     int n_kv_heads, n_q_heads, group;
     int n_part, n_rows, row_pitch;   // rows per KV head: row = node*group + jj
+    // chunk scores from per-tile logit sums (tile_sums == nullptr: none): extra workgroups of the same launch
+    const float *tile_sums;   // [n_kv_heads][tile_sums_stride]
+    float *scores;            // [n_kv_heads][n_chunks]
+    int64_t tile_sums_stride, n_tokens, n_chunks;
+    int chunk_size;           // multiple of 32
+    float scale;
 };
 hipError_t launch_combine(const CombineParams &p, hipStream_t stream);
 

@@ -196,6 +196,19 @@ verify_dma_kernel(const VerifyParams p)
         }
     }
 
+    // Tile sums for the chunk scores (see process_tile).  The store of a tile's sum waits until just
+    // before the next loads are issued: vmcnt counts loads and stores alike, in order, so a store younger
+    // than the loads a step waits for would put its own latency on that wait.
+    const bool scoring = p.tile_sums != nullptr && wave == 0 && blockIdx.z == 0 && !is_tree;   // wavefront-uniform
+    float score_parked = 0.f;
+    int64_t score_parked_tile = -1;
+    auto score_flush = [&]() {
+        if (scoring && score_parked_tile >= 0) {
+            if (lane == 0) p.tile_sums[(int64_t)h * p.tile_sums_stride + score_parked_tile] = score_parked;
+            score_parked_tile = -1;
+        }
+    };
+
     // One 32-key tile against all of this wavefront's rows.  RAGGED tiles (the last one of a
     // range, every tile of the tree split) mask keys; full tiles carry no masking code at all.
     // The body is laid out as three straight-line blocks so that the scheduler can overlap
@@ -225,6 +238,22 @@ verify_dma_kernel(const VerifyParams p)
                     sacc[rb][kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, sacc[rb][kb], 0, 0, 0);
                 }
             }
+        }
+        // Chunk scores ride along: the rows of the first tree node (rows 0..group-1, in wavefront 0) hold
+        // exactly the raw logits q.k that Eq. 2 sums; their sum over the tile's valid keys is parked
+        // until the next tile's loads are about to be issued (see score_flush), and the merge kernel
+        // turns tiles into chunks.
+        if (scoring && t0 < t_end) {
+            float ssum = 0.f;
+            const uint32_t ok = RAGGED ? (uint32_t)((t_end - t0 >= 32 ? 0xffffffffull : ((1ull << (t_end - t0)) - 1ull)) >> (quad * 4)) : 0xffffffffu;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float v = sacc[0][e >> 2][e & 3];
+                ssum += (!RAGGED || ((ok >> ((e >> 2) * 16 + (e & 3))) & 1u)) ? v : 0.f;
+            }
+            ssum = xrow_sum(ssum);                                   // the four lanes that share row j
+            score_parked = row16_sum(j < p.group ? ssum : 0.f);     // the group's heads
+            score_parked_tile = t0 >> 5;
         }
         // 8 keys x 4 consecutive columns per read, regrouped into one column x 8 keys per operand
         bf16x8 av[2][4];
@@ -328,10 +357,14 @@ verify_dma_kernel(const VerifyParams p)
     uint32_t use_stage = 0;          // stage of the tile being consumed
     int64_t t0_cur = t_begin;        // its first token
     auto step = [&](auto ragged_tag) {
-        wait_vmcnt<(NS - 2) * LPW>();                 // this wavefront's pieces of the next tile have landed
+        // this wavefront's pieces of the next tile have landed (a parked tile sum, stored just before
+        // the newest tile's loads were issued, is one more operation allowed to be outstanding)
+        if (scoring) wait_vmcnt<(NS - 2) * LPW + (NS > 2 ? 1 : 0)>();
+        else wait_vmcnt<(NS - 2) * LPW>();
         // ... and everyone's; all are done with the previous tile.  A bare s_barrier: __syncthreads() would add a
         // fence that waits for every outstanding load, i.e. for the whole prefetched ring.
         if (WR > 1) asm volatile("s_barrier" ::: "memory");
+        score_flush();
         issue_tile();                                 // refill the stage that the previous tile occupied
         process_tile(ragged_tag, lds + use_stage, t0_cur);
         use_stage += kStageBytes;
@@ -341,6 +374,7 @@ verify_dma_kernel(const VerifyParams p)
     const int n_full = is_tree ? 0 : (int)((t_end - t_begin) / kTileKeys);
     for (int it = 0; it < n_full; ++it) step(std::false_type{});
     for (int it = n_full; it < n_tiles; ++it) step(std::true_type{});
+    score_flush();
     wait_vmcnt<0>();   // drain the loads issued past the range before the workgroup's LDS is released
 
     // ---- write the partial: (m, l) and unnormalised O for every live row ----------------------

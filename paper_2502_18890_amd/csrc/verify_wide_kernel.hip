@@ -321,6 +321,19 @@ verify_wide_kernel(const VerifyParams p)
         }
     };
 
+    // Tile sums for the chunk scores (see pv_tile).  The store of a tile's sum waits until just before
+    // the next loads are issued: vmcnt counts loads and stores alike, in order, so a store younger than
+    // the loads a step waits for would put its own latency on that wait.
+    const bool scoring = p.tile_sums != nullptr && wave == 0 && blockIdx.z == 0 && !is_tree;   // wavefront-uniform
+    float score_parked = 0.f;
+    int64_t score_parked_tile = -1;
+    auto score_flush = [&]() {
+        if (scoring && score_parked_tile >= 0) {
+            if (lane == 0) p.tile_sums[(int64_t)h * p.tile_sums_stride + score_parked_tile] = score_parked;
+            score_parked_tile = -1;
+        }
+    };
+
     // ---- softmax of one tile's logits and O^T += V^T . P^T ----------------------------------------
     // RAGGED tiles (the last one of a range, every tile of the tree split) mask keys; full tiles
     // carry no masking code.
@@ -371,6 +384,23 @@ verify_wide_kernel(const VerifyParams p)
                     const u32x4 both = {r[4 * cb + 2 * s][0], r[4 * cb + 2 * s][1], r[4 * cb + 2 * s + 1][0], r[4 * cb + 2 * s + 1][1]};
                     vt[cb][s] = __builtin_bit_cast(bf16x8, both);
                 }
+        }
+
+        // Chunk scores ride along: the rows of the first tree node (rows 0..group-1 of the first row block,
+        // in wavefront 0 of every key group) hold exactly the raw logits q.k that Eq. 2 sums; their sum
+        // over the tile's valid keys is parked until the next tile's loads are about to be issued (see
+        // score_flush), and the merge kernel turns tiles into chunks.
+        if (L > 0 && scoring && t0 < t_end) {
+            float ssum = 0.f;
+            const uint32_t ok = RAGGED ? (uint32_t)((t_end - t0 >= 32 ? 0xffffffffull : ((1ull << (t_end - t0)) - 1ull)) >> (hh * 4)) : 0xffffffffu;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float v = sacc[0][e];
+                ssum += (!RAGGED || ((ok >> (8 * (e >> 2) + (e & 3))) & 1u)) ? v : 0.f;
+            }
+            ssum = swap32_sum(ssum);                                     // the two lanes that share row n32
+            score_parked = row16_sum(n32 < p.group ? ssum : 0.f);       // the group's heads (group <= 8: one 16-lane row)
+            score_parked_tile = t0 >> 5;
         }
 
         // m_run is a reference point, not necessarily the exact running maximum: the accumulators are
@@ -553,12 +583,16 @@ verify_wide_kernel(const VerifyParams p)
         auto sync_and_refill = [&]() {
             // this wavefront's pieces of the next group tile have landed: the NS-RES-1 issued after
             // it may still be in flight
-            wait_vmcnt<(NS - RES - 1) * LPW>();
+            // (a parked tile sum, stored just before the newest tile's loads were issued, is one more
+            // operation allowed to be outstanding)
+            if (scoring) wait_vmcnt<(NS - RES - 1) * LPW + (NS - RES - 1 > 0 ? 1 : 0)>();
+            else wait_vmcnt<(NS - RES - 1) * LPW>();
             // ... and everyone's; all are done with the previous group tile.  A bare s_barrier:
             // __syncthreads() would add a fence that waits for every outstanding load, i.e. for the
             // whole prefetched ring.
             if (F16) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wavefront's converted values are in LDS
             if (WR * KG > 1) asm volatile("s_barrier" ::: "memory");
+            score_flush();
             issue_tile();                                          // refills the stage the previous group tile occupied
         };
         auto run = [&](auto live_tag) {
@@ -590,6 +624,7 @@ verify_wide_kernel(const VerifyParams p)
         };
         if (nrb_live == NRB) run(std::integral_constant<int, NRB>{});
         else run(std::integral_constant<int, NRB - 1>{});   // round-robin dealing: never fewer than NRB-1 unless none at all
+        score_flush();
         wait_vmcnt<0>();   // drain the loads issued past the range before LDS is reused or released
     };
     float m_shift = 0.f;   // how far above the reference point the weights of the pass that counts were taken

@@ -33,7 +33,7 @@ def test_library_exports_every_declared_function(lib):
     assert names == ["ts_append_accepted", "ts_chunk_key_sums", "ts_chunk_list_admit", "ts_chunk_scores",
                      "ts_chunk_scores_from_sums", "ts_gather_chunks", "ts_partial_kv_attn", "ts_penalized_probs",
                      "ts_refresh_due", "ts_sample_tokens", "ts_sampling_workspace_bytes", "ts_stream_read_probe", "ts_strerror",
-                     "ts_topk_chunks", "ts_tree_verify_attn", "ts_tune_set", "ts_version", "ts_workspace_bytes"]
+                     "ts_topk_chunks", "ts_tree_verify_attn", "ts_tree_verify_attn_scored", "ts_tune_set", "ts_version", "ts_workspace_bytes"]
     for n in names:
         assert hasattr(lib, n), n
     assert lib.ts_version() >= 100
@@ -131,6 +131,21 @@ def test_attention_calls_reject_bad_arguments(lib, binding):
     assert tv([-1, 0], hq=3) == TS_ERR_SHAPE
     assert tv([-1, 0], ws_=None) == TS_ERR_WORKSPACE and tv([-1, 0], wsb=100) == TS_ERR_WORKSPACE
     assert tv([-1, 0], view=_view(binding, d=96)) == TS_ERR_UNSUPPORTED
+
+    def tvs(parent, chunk=64, scores=0x8000, view=None, wsb=big):
+        par = (ctypes.c_int32 * len(parent))(*parent)
+        return lib.ts_tree_verify_attn_scored(ctypes.byref(view if view is not None else _view(binding)), q, 4, 0x6000, 0x7000,
+                                              par, len(parent), 1.0, chunk, scores, out, None, ws, wsb, None)
+    assert tvs([-1, 0], scores=None) == TS_ERR_NULL
+    assert tvs([-1, 0], chunk=16) == TS_ERR_UNSUPPORTED and tvs([-1, 0], chunk=48) == TS_ERR_UNSUPPORTED   # whole 32-key tiles only
+    assert tvs([-1, 0], chunk=2048) == TS_ERR_UNSUPPORTED
+    assert tvs([-1, 0], view=_view(binding, n=0, k=None, v=None)) == TS_ERR_SHAPE      # nothing to score
+    assert tvs([0, 0]) == TS_ERR_TREE
+    # the scored call needs room for one sum per 32-key tile on top of the plain call's workspace
+    need_plain = binding.workspace_bytes(binding.OP_TREE_VERIFY, 4, 2, 100, 2)
+    need_scored = binding.workspace_bytes(binding.OP_TREE_VERIFY_SCORED, 4, 2, 100, 2)
+    assert need_scored >= need_plain + 2 * 4 * 4
+    assert tvs([-1, 0], wsb=need_plain) == TS_ERR_WORKSPACE
 
 
 def test_tune_set(lib):

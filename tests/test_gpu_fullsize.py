@@ -1,6 +1,7 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times: one
 layer of each large workload is generated on the device, the whole path runs through the C ABI,
-and the fp64 oracle checks every chunk score, the selection (bit-exact from the GPU's scores),
+and the fp64 oracle checks every chunk score (from the scoring pass and from the verification pass that
+leaves them), the selection (bit-exact from the GPU's scores),
 the whole partial-attention output, and a sample of tree-verification rows it computes one by one."""
 import numpy as np
 import pytest
@@ -25,13 +26,20 @@ def test_full_size_layer(ci):
     out_p, lse_p = ts.partial_kv_attn(x["q"], x["k"], x["v"], idx, cfg.chunk, cfg.scale, want_lse=True)
     out_v, lse_v = ts.tree_verify_attn(x["q_tree"], x["k"], x["v"], x["k_tree"], x["v_tree"], x["parent"], cfg.scale,
                                        want_lse=True)
+    # the call the benchmark's step uses: verification that also leaves the chunk scores (tree node 0 carries q)
+    out_s, lse_s, sc_s = ts.tree_verify_attn(x["q_tree"], x["k"], x["v"], x["k_tree"], x["v_tree"], x["parent"], cfg.scale,
+                                             want_lse=True, score_chunk=cfg.chunk)
     torch.cuda.synchronize()
+    assert torch.equal(out_s, out_v) and torch.equal(lse_s, lse_v)
 
     bits = S.torch_bf16_to_bits
     q, k, v = bits(x["q"]), bits(x["k"]), bits(x["v"])
     # chunk scores: all of them
     ref_sc = oracle.chunk_scores(q, k, cfg.chunk, cfg.scale)
     assert_close(sc.cpu().numpy(), ref_sc, "scores cfg%d" % ci)
+    assert_close(sc_s.cpu().numpy(), ref_sc, "scores from the verification pass cfg%d" % ci)
+    idx_s = ts.topk_chunks(sc_s, cfg.n_sink, cfg.k).cpu().numpy()
+    np.testing.assert_array_equal(idx_s, oracle.topk_chunks(sc_s.cpu().numpy(), cfg.n_sink, cfg.k))
     # selection: bit-exact from the same fp32 score vector
     idx_h = idx.cpu().numpy()
     np.testing.assert_array_equal(idx_h, oracle.topk_chunks(sc.cpu().numpy(), cfg.n_sink, cfg.k))

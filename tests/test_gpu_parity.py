@@ -195,6 +195,36 @@ def test_verify_shapes(ts, hq, hkv, n, t):
     assert_close(lse, rlse, "verify lse")
 
 
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("hq,hkv,n,t,chunk", [
+    (4, 4, 1000, 8, 64), (32, 32, 1567, 32, 64), (8, 2, 2500, 16, 32), (32, 8, 4133, 32, 64), (40, 8, 3001, 64, 128),
+    (6, 2, 777, 5, 32), (12, 2, 16384, 16, 64), (16, 2, 33, 20, 64), (8, 8, 1, 3, 32), (48, 8, 2300, 100, 96),
+    (64, 8, 900, 128, 1024), (5, 1, 6500, 7, 64),
+])
+def test_verify_scored_leaves_the_chunk_scores_of_the_root_query(ts, variant, hq, hkv, n, t, chunk):
+    """The scored call returns the same attention output as the plain one, bit for bit, and the chunk
+    scores that the scoring pass gives for the query of tree node 0 -- for every kernel shape (rows of
+    node 0 in the 16x16x32 kernel, in the first row block of the 32x32x16 kernel, with key groups)."""
+    import torch
+    c = _case(33, hq, hkv, n, t)
+    parent = _random_parent(c["rng"], t)
+    args = (dev(c["q_tree"]), dev(c["k"]), dev(c["v"]), dev(c["k_tree"]), dev(c["v_tree"]), parent, SCALE)
+    try:
+        ts.tune_set("verify_variant", variant)
+        plain = ts.tree_verify_attn(*args)
+        out, lse, scores = ts.tree_verify_attn(*args, want_lse=True, score_chunk=chunk)
+    finally:
+        ts.tune_set("verify_variant", 0)
+    assert torch.equal(plain, out)
+    ref, rlse = oracle.tree_verify(c["q_tree"], c["k"], c["v"], c["k_tree"], c["v_tree"], parent, SCALE)
+    assert_close(_np(out), ref, "scored verify out")
+    assert_close(_np(lse), rlse, "scored verify lse")
+    assert_close(_np(scores), oracle.chunk_scores(c["q_tree"][0], c["k"], chunk, SCALE), "scores from the verification pass")
+    # the same numbers as the scoring pass proper, to rounding order
+    direct = ts.chunk_scores(dev(c["q_tree"])[0].contiguous(), dev(c["k"]), chunk, SCALE)
+    np.testing.assert_allclose(_np(scores), _np(direct), rtol=0, atol=2e-4)
+
+
 @pytest.mark.parametrize("kind", ["chain", "star", "fixed"])
 def test_verify_tree_kinds(ts, kind):
     c = _case(8, 8, 2, 200, 8)

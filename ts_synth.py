@@ -157,8 +157,8 @@ def make_layer(cfg: SynthConfig, layer: int = 0, n_tokens: Optional[int] = None,
                n_tree: Optional[int] = None, tree_kind: Optional[str] = None) -> dict:
     """One layer's inputs as numpy uint16 (bf16 bits) arrays.
 
-    q [Hq,d]; q_tree [T,Hq,d]; k_tree, v_tree [T,Hkv,d]; k, v [Hkv,N,d]; parent [T] int32;
-    planted [Hkv, n_planted] chunk ids.
+    q [Hq,d]; q_tree [T,Hq,d] with q_tree[0] = q; k_tree, v_tree [T,Hkv,d]; k, v [Hkv,N,d];
+    parent [T] int32; planted [Hkv, n_planted] chunk ids.
     """
     n_tokens = cfg.n_tokens if n_tokens is None else n_tokens
     n_tree = cfg.n_tree if n_tree is None else n_tree
@@ -166,6 +166,7 @@ def make_layer(cfg: SynthConfig, layer: int = 0, n_tokens: Optional[int] = None,
     rng = _rng(cfg, layer, 1)
     q = f32_to_bf16_bits(rng.standard_normal((hq, d), dtype=np.float32))
     q_tree = f32_to_bf16_bits(rng.standard_normal((n_tree, hq, d), dtype=np.float32))
+    q_tree[0] = q      # tree node 0 is the token the iteration starts from: the query of the draft pass and of the scores
     k_tree = f32_to_bf16_bits(rng.standard_normal((n_tree, hkv, d), dtype=np.float32))
     v_tree = f32_to_bf16_bits(rng.standard_normal((n_tree, hkv, d), dtype=np.float32))
     k = rng.standard_normal((hkv, n_tokens, d), dtype=np.float32)
@@ -203,6 +204,7 @@ def make_layer_torch(cfg: SynthConfig, layer: int, device, n_tokens: Optional[in
 
     q = normal(hq, d).to(torch.bfloat16)
     q_tree = normal(n_tree, hq, d).to(torch.bfloat16)
+    q_tree[0] = q      # tree node 0 is the token the iteration starts from: the query of the draft pass and of the scores
     k_tree = normal(n_tree, hkv, d).to(torch.bfloat16)
     v_tree = normal(n_tree, hkv, d).to(torch.bfloat16)
     k = torch.empty(hkv, n_tokens, d, device=device, dtype=torch.bfloat16)
