@@ -225,6 +225,17 @@ def test_verify_scored_leaves_the_chunk_scores_of_the_root_query(ts, variant, hq
     np.testing.assert_allclose(_np(scores), _np(direct), rtol=0, atol=2e-4)
 
 
+def test_verify_scored_token_major_layout(ts):
+    """K and V stored [N, Hkv, d] and passed as strided views: same scores, same output."""
+    c = _case(34, 8, 2, 1500, 12)
+    parent = _random_parent(c["rng"], 12)
+    kd = dev(np.ascontiguousarray(c["k"].transpose(1, 0, 2))).transpose(0, 1)
+    vd = dev(np.ascontiguousarray(c["v"].transpose(1, 0, 2))).transpose(0, 1)
+    out, scores = ts.tree_verify_attn(dev(c["q_tree"]), kd, vd, dev(c["k_tree"]), dev(c["v_tree"]), parent, SCALE, score_chunk=64)
+    assert_close(_np(out), oracle.tree_verify(c["q_tree"], c["k"], c["v"], c["k_tree"], c["v_tree"], parent, SCALE)[0], "out")
+    assert_close(_np(scores), oracle.chunk_scores(c["q_tree"][0], c["k"], 64, SCALE), "scores")
+
+
 @pytest.mark.parametrize("kind", ["chain", "star", "fixed"])
 def test_verify_tree_kinds(ts, kind):
     c = _case(8, 8, 2, 200, 8)
