@@ -4,7 +4,7 @@
 //   m* = max m_i,  l* = sum l_i 2^(m_i - m*),  out = sum O_i 2^(m_i - m*) / l*,
 // and the natural-log sum of exponentials is (m* + log2 l*) ln 2.
 // One wavefront per row, two output columns per lane; the weights are computed once, one partial
-// per lane, and broadcast as the partials stream in, eight loads in flight.
+// per lane, and broadcast as the partials stream in, sixteen loads in flight.
 #include "ts_device.hpp"
 #include "ts_internal.hpp"
 
@@ -59,13 +59,21 @@ __global__ void __launch_bounds__(256) combine_kernel(const CombineParams p)
         }
         const int n_here = p.n_part - base < 64 ? p.n_part - base : 64;
         int u0 = 0;
-        for (; u0 + 8 <= n_here; u0 += 8) {   // eight partials in flight
-            f32x2 o[8];
+        for (; u0 + 16 <= n_here; u0 += 16) {   // sixteen partials in flight
+            f32x2 o[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < 16; ++u)
                 o[u] = *reinterpret_cast<const f32x2 *>(p.ws_o + (first + (int64_t)(base + u0 + u) * pitch) * kHeadDim + lane * 2);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) acc += o[u] * __shfl(w, u0 + u, 64);
+            for (int u = 0; u < 16; ++u) acc += o[u] * __shfl(w, u0 + u, 64);
+        }
+        for (; u0 + 4 <= n_here; u0 += 4) {
+            f32x2 o[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                o[u] = *reinterpret_cast<const f32x2 *>(p.ws_o + (first + (int64_t)(base + u0 + u) * pitch) * kHeadDim + lane * 2);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc += o[u] * __shfl(w, u0 + u, 64);
         }
         for (; u0 < n_here; ++u0) {
             const f32x2 o = *reinterpret_cast<const f32x2 *>(p.ws_o + (first + (int64_t)(base + u0) * pitch) * kHeadDim + lane * 2);
