@@ -66,7 +66,10 @@ bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, bo
     if (n_tokens > 0) {
         const int row_tiles = (pl->n_rows + pl->shape.rows_per_wg - 1) / pl->shape.rows_per_wg;
         const int64_t per_split = (int64_t)n_kv_heads * row_tiles;          // workgroups per split index
-        int64_t want = (int64_t)kNumCUs * pl->shape.wg_per_cu / per_split - 1;   // - 1: the tree split
+        // - 1: the tree split.  Not for the two-wavefront 16x16x32 kernel: its tree workgroups are over in a
+        // few microseconds, so letting them (and the cache workgroups that then start late) run in slots that
+        // free up early costs less than leaving one slot in 32 idle for the whole pass (257 vs 260 us at 100K).
+        int64_t want = (int64_t)kNumCUs * pl->shape.wg_per_cu / per_split - (pl->shape.kernel_id == ts::kNarrow_32 ? 0 : 1);
         const int64_t cap_traffic = (n_tokens * 512 / 4) / ((int64_t)pl->n_rows_pad * 520) + 1;  // partials <= 1/4 of K/V
         if (want > cap_traffic) want = cap_traffic;
         if (g_tune.verify_splits > 0) want = g_tune.verify_splits;
