@@ -132,7 +132,11 @@ bool ts::verify_shape(int n_rows, int variant, VerifyShape *out)
     const int tiles = (n_rows + 383) / 384;
     const int r = ((n_rows + tiles - 1) / tiles + 31) / 32 * 32;   // rows per tile, balanced
     if (r <= 32) *out = variant == 2 ? VerifyShape{kWide_1x1b, 32, 2} : VerifyShape{kWide_1x1, 32, 3};
-    else if (r <= 64) *out = variant == 1 ? VerifyShape{kWide_1x2h, 64, 2} : VerifyShape{kWide_1x2, 64, 2};
+    else if (r <= 64) {
+        if (variant == 1) *out = VerifyShape{kWide_1x2h, 64, 2};
+        else if (variant == 2) *out = VerifyShape{kWide_1x2, 64, 2};
+        else *out = VerifyShape{kWide_1x2k4, 64, 1};
+    }
     else if (r <= 128) {
         if (variant == 1) *out = VerifyShape{kWide_1x4h, 128, 2};
         else if (variant == 2) *out = VerifyShape{kWide_1x4, 128, 2};

@@ -54,6 +54,7 @@ enum VerifyKernelId {
     kWide_1x1,
     kWide_1x1b,       // deeper ring, two workgroups per CU
     kWide_1x2,
+    kWide_1x2k4,      // four key groups
     kWide_1x4,
     kWide_1x4k3,      // three key groups, query fragments in LDS
     kWide_2x4,

@@ -749,6 +749,7 @@ hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t 
         case kWide_1x1: return launch_one<1, 1, 1, 3, 2, false>(p, stream);
         case kWide_1x1b: return launch_one<1, 1, 1, 4, 2, false>(p, stream);
         case kWide_1x2: return launch_one<1, 2, 1, 4, 2, false>(p, stream);
+        case kWide_1x2k4: return launch_one<1, 2, 4, 2, 2, false>(p, stream);
         case kWide_1x4: return launch_one<1, 4, 1, 4, 2, false>(p, stream);
         case kWide_1x4k3: return launch_one<1, 4, 3, 2, 3, true>(p, stream);
         case kWide_2x4: return launch_one<2, 4, 1, 6, 1, false>(p, stream);
