@@ -319,6 +319,11 @@ def main():
         "breakdown_us_per_layer": {k: round(v, 3) for k, v in parts.items()},
         "breakdown_spread_us_per_layer": {k: {q: round(v, 3) for q, v in st.items() if q != "mean"} for k, st in stats.items()},
         "verify_plus_partial_us_per_layer": round(parts["verify"] + parts["partial"], 3),
+        # Alg. 1 rebuilds the partial cache once per |B| - |S| = k * chunk accepted tokens: the scoring pass and the
+        # selection, spread over those tokens (what they cost when they are passes of their own)
+        "rebuild_amortised": {"scores_plus_topk_us_per_layer": round(parts["scores"] + parts["topk"], 3),
+                              "tokens_between_rebuilds": cfg.k * cfg.chunk,
+                              "us_per_layer_per_accepted_token": round((parts["scores"] + parts["topk"]) / (cfg.k * cfg.chunk), 5)},
         "cache_maintenance_us_per_layer": {k: round(v, 3) for k, v in maint.items()},
         "sampling_us_per_step": dict({k: round(v, 3) for k, v in sampling.items()}, rows=t, vocab=vocab, window=1024,
                                      penalized_probs_gbs=round(sampling_bytes / (sampling["penalized_probs"] * 1e-6) / 1e9, 1)),
