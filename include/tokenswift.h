@@ -83,7 +83,8 @@ int ts_version(void);
  * (0 on invalid arguments).  op is TS_OP_PARTIAL_ATTN (n_sel, chunk_size used; n_tree ignored)
  * or TS_OP_TREE_VERIFY / TS_OP_TREE_VERIFY_SCORED (n_tree used; n_sel, chunk_size ignored).  The workspace holds the
  * per-split softmax partials (running max, sum of exponentials, unnormalised output) that a
- * second kernel merges; its contents are scratch and need no initialisation.
+ * second kernel merges (for TS_OP_TREE_VERIFY_SCORED also one logit sum per KV head and 32-key tile
+ * of the cache); its contents are scratch and need no initialisation.
  */
 size_t ts_workspace_bytes(int op, int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree,
                           int n_sel, int chunk_size);
