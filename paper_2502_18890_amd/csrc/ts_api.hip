@@ -171,7 +171,7 @@ const char *ts_strerror(int status)
     }
 }
 
-int ts_version(void) { return 100; }
+int ts_version(void) { return 200; }
 
 int ts_tune_set(const char *name, int value)
 {
