@@ -43,41 +43,54 @@ __global__ void __launch_bounds__(256) combine_kernel(const CombineParams p)
     const int64_t first = (int64_t)h * p.n_part * pitch + row;   // partial pp at first + pp*pitch
 
     // Lane pp holds the weight of partials pp, pp+64, ...: w = 2^(m_pp - m*), and l* = sum w l.
-    float mstar = kNegBig;
-    for (int pp = lane; pp < p.n_part; pp += 64)
-        mstar = fmaxf(mstar, p.ws_ml[(first + (int64_t)pp * pitch) * 2]);
-    mstar = wave_max(mstar);
-
     f32x2 acc = {0.f, 0.f};
     float lsum = 0.f;
-    for (int base = 0; base < p.n_part; base += 64) {
-        float w = 0.f;
-        if (base + lane < p.n_part) {
-            const f32x2 ml = *reinterpret_cast<const f32x2 *>(p.ws_ml + (first + (int64_t)(base + lane) * pitch) * 2);
-            w = fast_exp2(ml[0] - mstar);
-            lsum = fmaf(w, ml[1], lsum);
-        }
-        const int n_here = p.n_part - base < 64 ? p.n_part - base : 64;
-        int u0 = 0;
-        for (; u0 + 16 <= n_here; u0 += 16) {   // sixteen partials in flight
-            f32x2 o[16];
+    float mstar = kNegBig;
+    auto o_at = [&](int pp) {
+        return *reinterpret_cast<const f32x2 *>(p.ws_o + (first + (int64_t)pp * pitch) * kHeadDim + lane * 2);
+    };
+    if (p.n_part <= 64) {
+        // The usual case.  The first sixteen partials' outputs are requested before the (m, l) pairs are
+        // needed, so the two rounds of memory latency overlap instead of following each other.
+        f32x2 ml = {kNegBig, 0.f};
+        if (lane < p.n_part) ml = *reinterpret_cast<const f32x2 *>(p.ws_ml + (first + (int64_t)lane * pitch) * 2);
+        f32x2 o[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u)
-                o[u] = *reinterpret_cast<const f32x2 *>(p.ws_o + (first + (int64_t)(base + u0 + u) * pitch) * kHeadDim + lane * 2);
+        for (int u = 0; u < 16; ++u) o[u] = u < p.n_part ? o_at(u) : f32x2{0.f, 0.f};
+        mstar = wave_max(ml[0]);
+        const float w = lane < p.n_part ? fast_exp2(ml[0] - mstar) : 0.f;
+        lsum = w * ml[1];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) acc += o[u] * __shfl(w, u, 64);   // weight 0 beyond n_part
+        int u0 = 16;
+        for (; u0 + 16 <= p.n_part; u0 += 16) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) o[u] = o_at(u0 + u);
 #pragma unroll
             for (int u = 0; u < 16; ++u) acc += o[u] * __shfl(w, u0 + u, 64);
         }
-        for (; u0 + 4 <= n_here; u0 += 4) {
-            f32x2 o[4];
+        for (; u0 < p.n_part; ++u0) acc += o_at(u0) * __shfl(w, u0, 64);
+    } else {
+        for (int pp = lane; pp < p.n_part; pp += 64)
+            mstar = fmaxf(mstar, p.ws_ml[(first + (int64_t)pp * pitch) * 2]);
+        mstar = wave_max(mstar);
+        for (int base = 0; base < p.n_part; base += 64) {
+            float w = 0.f;
+            if (base + lane < p.n_part) {
+                const f32x2 ml = *reinterpret_cast<const f32x2 *>(p.ws_ml + (first + (int64_t)(base + lane) * pitch) * 2);
+                w = fast_exp2(ml[0] - mstar);
+                lsum = fmaf(w, ml[1], lsum);
+            }
+            const int n_here = p.n_part - base < 64 ? p.n_part - base : 64;
+            int u0 = 0;
+            for (; u0 + 16 <= n_here; u0 += 16) {   // sixteen partials in flight
+                f32x2 o[16];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                o[u] = *reinterpret_cast<const f32x2 *>(p.ws_o + (first + (int64_t)(base + u0 + u) * pitch) * kHeadDim + lane * 2);
+                for (int u = 0; u < 16; ++u) o[u] = o_at(base + u0 + u);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) acc += o[u] * __shfl(w, u0 + u, 64);
-        }
-        for (; u0 < n_here; ++u0) {
-            const f32x2 o = *reinterpret_cast<const f32x2 *>(p.ws_o + (first + (int64_t)(base + u0) * pitch) * kHeadDim + lane * 2);
-            acc += o * __shfl(w, u0, 64);
+                for (int u = 0; u < 16; ++u) acc += o[u] * __shfl(w, u0 + u, 64);
+            }
+            for (; u0 < n_here; ++u0) acc += o_at(base + u0) * __shfl(w, u0, 64);
         }
     }
     const float lstar = wave_sum(lsum);
