@@ -60,7 +60,7 @@ bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, bo
     const int group = n_q_heads / n_kv_heads;
     pl->n_rows = group * n_tree;
     pl->n_rows_pad = (pl->n_rows + 15) / 16 * 16;
-    if (!ts::verify_shape(pl->n_rows, g_tune.verify_variant, &pl->shape)) return false;
+    if (!ts::verify_shape(pl->n_rows, n_kv_heads, g_tune.verify_variant, &pl->shape)) return false;
     int n_split = 0;
     int64_t split_len = 32;
     if (n_tokens > 0) {
@@ -118,7 +118,7 @@ bool partial_chunk_ok(int chunk_size) { return chunk_size >= 16 && chunk_size <=
 // shapes; variant 1..3 select alternatives where there are any (all produce the same results):
 // 1 swaps the precision of the second product (fp16 where the default is bf16 + residual and
 // the other way round), 2 and 3 other workgroup shapes.
-bool ts::verify_shape(int n_rows, int variant, VerifyShape *out)
+bool ts::verify_shape(int n_rows, int n_kv_heads, int variant, VerifyShape *out)
 {
     if (n_rows < 1 || n_rows > TS_MAX_GROUP * TS_MAX_TREE) return false;
     if (variant == 0 && n_rows <= 16) {
@@ -141,6 +141,9 @@ bool ts::verify_shape(int n_rows, int variant, VerifyShape *out)
         if (variant == 1) *out = VerifyShape{kWide_1x4h, 128, 2};
         else if (variant == 2) *out = VerifyShape{kWide_1x4, 128, 2};
         else if (variant == 3) *out = VerifyShape{kWide_1x4k2h, 128, 1};
+        // many KV heads: each workgroup's range is long either way, and two workgroups of four wavefronts per
+        // CU measured 2-5 % faster than one of twelve; with few heads the extra partials cost more than that
+        else if (n_kv_heads >= 16) *out = VerifyShape{kWide_1x4, 128, 2};
         else *out = VerifyShape{kWide_1x4k3, 128, 1};
     } else if (r <= 256) {
         if (variant == 1) *out = VerifyShape{kWide_1x8, 256, 1};
