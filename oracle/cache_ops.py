@@ -7,7 +7,8 @@ with the GPU library.  Passages followed:
   refresh_due          Alg. 1, the condition that guards the "Dynamic KV Cache Update" step: more than |B| - |S|
                        tokens were added since the last rebuild.
   chunk_list_admit     Sec. 3.3 "Dynamic KV Cache Updates": new tokens replace the least important
-                       entries of C_p, from position |B|-1 towards |S| (here one chunk per entry).
+                       entries of C_p, from position |B|-1 towards |S| (here one chunk per entry, taken
+                       when the chunk's first token arrives; a chunk is never listed twice).
   gather_chunks        Alg. 1: C_p = {C_full[0:|S|], Top-K(C_full)} as a buffer of its own.
   chunk_key_sums       (Eq. 2 is linear in the key) the per-chunk sums of the keys;
   scores_from_sums     Eq. 2 averaged per chunk, evaluated as (sum_j q_j) . (sum_t k_t) / |chunk|.
@@ -35,13 +36,29 @@ def refresh_due(n_tokens, n_tokens_at_refresh, budget_tokens, sink_tokens):
     return (n_tokens - n_tokens_at_refresh) > (budget_tokens - sink_tokens)
 
 
-def chunk_list_admit(chunk_idx, n_sink, first_new_chunk, n_new):
-    """chunk_idx [Hkv, n_sel] int32 ordered by decreasing importance after the sink entries."""
+def chunk_list_admit(chunk_idx, n_sink, base_chunk, first_new_chunk, n_new):
+    """chunk_idx [Hkv, n_sel] int32: n_sink sink entries, then entries by decreasing importance; no chunk twice.
+
+    New tokens enter C_p as they are generated and take its positions from the last one towards the
+    sink.  At chunk granularity: base_chunk is the chunk that receives the first token generated after
+    the last rebuild; chunk c (>= base_chunk) owns position n_sel - 1 - (c - base_chunk) from the moment
+    its first token exists.  A chunk already listed (the partly filled last chunk, if the rebuild
+    selected it) is not listed a second time: it trades places with the entry at its position, and
+    nothing is evicted for it; a chunk among the sink entries stays where it is."""
     out = np.array(chunk_idx, dtype=np.int32, copy=True)
     n_sel = out.shape[1]
-    assert 0 <= n_new <= n_sel - n_sink
-    for i in range(n_new):                 # the i-th new chunk evicts the i-th least important entry
-        out[:, n_sel - 1 - i] = first_new_chunk + i
+    assert n_new >= 0 and first_new_chunk >= base_chunk
+    assert first_new_chunk + n_new - base_chunk <= n_sel - n_sink      # else a rebuild is due instead
+    for h in range(out.shape[0]):
+        for c in range(first_new_chunk, first_new_chunk + n_new):
+            pos = n_sel - 1 - (c - base_chunk)
+            where = [j for j in range(n_sel) if out[h, j] == c]
+            assert len(where) <= 1
+            if not where:
+                out[h, pos] = c                    # evicts the least important entry still there
+            elif where[0] >= n_sink and where[0] != pos:
+                out[h, where[0]] = out[h, pos]
+                out[h, pos] = c
     return out
 
 

@@ -29,42 +29,40 @@ def penalized_probs(logits, window, temperature, theta):
 
 
 def pool_threshold(p_row, method, param, param2=0.0):
-    """Probability threshold tau of the pool {v : p[v] >= tau} for one row.
-
-    The product p_base * p_max and the comparison are taken in float32 when the row is float32
-    (the precision in which the GPU takes the same decision)."""
-    p = np.asarray(p_row)
+    """Probability threshold tau of the pool {v : p[v] >= tau} for one row, in float64 (the row is widened
+    exactly; the result is a Python float)."""
+    p = np.asarray(p_row, dtype=np.float64)
     if method == FULL:
-        return p.dtype.type(0)
+        return 0.0
     if method == MIN_P:
-        return p.dtype.type(param) * p.max()
+        return float(param) * float(p.max())
     if method == TOP_P:
         # smallest set of most probable tokens whose mass reaches `param`: walk the tokens in order of
         # decreasing probability; tokens tied with the last one taken are all kept
-        order = np.argsort(-p.astype(np.float64), kind="stable")
+        order = np.argsort(-p, kind="stable")
         mass = 0.0
-        tau = p[order[-1]]
+        tau = float(p[order[-1]])
         for v in order:
             mass += float(p[v])
             if mass >= param:
-                tau = p[v]
+                tau = float(p[v])
                 break
         return tau
     if method == ETA:
         # eta = min(epsilon, alpha * exp(-h)), h = entropy of the row (natural log); param = epsilon, param2 = alpha
-        q = p.astype(np.float64)
-        h = -float(np.sum(np.where(q > 0, q * np.log(np.where(q > 0, q, 1.0)), 0.0)))
-        return p.dtype.type(min(float(param), float(param2) * np.exp(-h)))
+        h = -float(np.sum(np.where(p > 0, p * np.log(np.where(p > 0, p, 1.0)), 0.0)))
+        return min(float(param), float(param2) * float(np.exp(-h)))
     raise ValueError(method)
 
 
-def sample(p_row, method, param, u, param2=0.0):
-    """-> (token, pool_mass, margin): margin = distance of u*pool_mass to the nearest step of the
-    pool's cumulative distribution, relative to pool_mass (how decisive the draw was)."""
-    p = np.asarray(p_row)
-    tau = pool_threshold(p, method, param, param2)
-    in_pool = p >= tau
-    w = np.where(in_pool, p.astype(np.float64), 0.0)
+def sample_from_pool(p_row, tau, u):
+    """Draw from the pool {v : p[v] >= tau} with the renormalised probabilities, by inverting the pool's
+    cumulative distribution (taken in order of token id) at u.
+    -> (token, pool_mass, margin): margin = distance of u*pool_mass to the nearest step of that
+    cumulative distribution, relative to pool_mass (how decisive the draw was)."""
+    p = np.asarray(p_row, dtype=np.float64)
+    in_pool = p >= float(tau)
+    w = np.where(in_pool, p, 0.0)
     cdf = np.cumsum(w)
     mass = cdf[-1]
     target = float(u) * mass
@@ -73,3 +71,8 @@ def sample(p_row, method, param, u, param2=0.0):
     steps = cdf[in_pool]
     margin = float(np.min(np.abs(steps - target))) / mass
     return tok, mass, margin
+
+
+def sample(p_row, method, param, u, param2=0.0):
+    """-> (token, pool_mass, margin) for the pool of `method` (see pool_threshold and sample_from_pool)."""
+    return sample_from_pool(p_row, pool_threshold(p_row, method, param, param2), u)

@@ -47,13 +47,45 @@ def test_refresh_due_matches_the_loop_condition_of_alg1():
 
 def test_chunk_list_admit_evicts_from_the_tail_towards_the_sink():
     idx = np.array([[0, 7, 3, 9, 5], [0, 2, 8, 4, 6]], dtype=np.int32)   # sink 0, then decreasing importance
-    out = C.chunk_list_admit(idx, 1, 20, 2)
+    out = C.chunk_list_admit(idx, 1, 20, 20, 2)
     assert out.tolist() == [[0, 7, 3, 21, 20], [0, 2, 8, 21, 20]]
-    assert np.array_equal(C.chunk_list_admit(idx, 1, 20, 0), idx)
-    full = C.chunk_list_admit(idx, 1, 30, 4)
+    assert np.array_equal(C.chunk_list_admit(idx, 1, 20, 20, 0), idx)
+    full = C.chunk_list_admit(idx, 1, 30, 30, 4)
     assert full[:, 0].tolist() == [0, 0] and sorted(full[0, 1:].tolist()) == [30, 31, 32, 33]
     with pytest.raises(AssertionError):
-        C.chunk_list_admit(idx, 1, 30, 5)          # would overwrite the sink: a rebuild is due instead
+        C.chunk_list_admit(idx, 1, 30, 30, 5)      # would overwrite the sink: a rebuild is due instead
+    with pytest.raises(AssertionError):
+        C.chunk_list_admit(idx, 1, 30, 29, 1)      # a chunk from before the rebuild is no new chunk
+
+
+def test_chunk_list_admit_positions_follow_the_chunk_not_the_call():
+    """Successive calls walk towards the sink (they do not start at the tail again), and admitting the
+    same chunk again -- its later tokens arriving -- changes nothing."""
+    idx = np.array([[0, 7, 3, 9, 5, 11]], dtype=np.int32)
+    a = C.chunk_list_admit(idx, 1, 20, 20, 1)
+    assert a.tolist() == [[0, 7, 3, 9, 5, 20]]
+    b = C.chunk_list_admit(a, 1, 20, 20, 2)        # chunk 20 again (more of its tokens) and chunk 21
+    assert b.tolist() == [[0, 7, 3, 9, 21, 20]]
+    c = C.chunk_list_admit(b, 1, 20, 22, 2)
+    assert c.tolist() == [[0, 7, 23, 22, 21, 20]]
+    one_go = C.chunk_list_admit(idx, 1, 20, 20, 4)
+    assert one_go.tolist() == c.tolist()
+
+
+def test_chunk_list_admit_never_lists_a_chunk_twice():
+    """The partly filled last chunk may already be listed when its next token arrives (the rebuild selected
+    it): it moves to its position, the entry there takes its old place, nothing is evicted.  A duplicate
+    would count twice in the softmax of the drafting pass."""
+    idx = np.array([[0, 7, 12, 9, 5], [0, 2, 8, 4, 12], [12, 3, 8, 4, 6]], dtype=np.int32)
+    out = C.chunk_list_admit(idx, 1, 12, 12, 1)
+    assert out[0].tolist() == [0, 7, 5, 9, 12]     # traded places with the tail entry
+    assert out[1].tolist() == [0, 2, 8, 4, 12]     # already at its position
+    assert out[2].tolist() == [12, 3, 8, 4, 6]     # a sink entry stays where it is; nothing evicted
+    for row in C.chunk_list_admit(idx, 1, 12, 12, 2):
+        assert len(set(row.tolist())) == len(row)
+    # the key set the list stands for: union of the old one and the new chunk, minus what was evicted
+    before, after = set(idx[0].tolist()), set(out[0].tolist())
+    assert after == before
 
 
 def test_gather_then_dense_attention_equals_partial_attention():
