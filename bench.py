@@ -241,7 +241,7 @@ def main():
         "key_sums_full_rebuild": lambda i, x: ts.chunk_key_sums(x["k"], cfg.chunk, out=ksum[i]),
         "key_sums_last_chunk": lambda i, x: ts.chunk_key_sums(x["k"], cfg.chunk, out=ksum[i], chunk_begin=cfg.n_chunks - 1),
         "append_accepted_4": lambda i, x: ts.append_accepted(x["k"], x["v"], n - len(acc), x["k_tree"], x["v_tree"], acc),
-        "chunk_list_admit_1": lambda i, x: ts.chunk_list_admit(idx, cfg.n_sink, cfg.n_chunks - 1, 1),
+        "chunk_list_admit_1": lambda i, x: ts.chunk_list_admit(idx, cfg.n_sink, cfg.n_chunks - 1, cfg.n_chunks - 1, 1),
         "gather_chunks": lambda i, x: ts.gather_chunks(x["k"], x["v"], idx, cfg.chunk),
     }
     do_topk(layers[0])

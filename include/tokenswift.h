@@ -210,13 +210,28 @@ int ts_refresh_due(int64_t n_tokens, int64_t n_tokens_at_refresh, int64_t budget
 
 /*
  * Between rebuilds, newly generated tokens take the place of the least important entries of
- * C_p, from its last position towards the sink (Sec. 3.3).  At chunk granularity: for every KV
- * head, entry n_sel - 1 - i of the chunk list becomes first_new_chunk + i, for i < n_new_chunks
- * (the list is ordered by decreasing importance, so its tail holds the least important chunks).
+ * C_p, from its last position towards the sink (Sec. 3.3).  At chunk granularity: base_chunk is the
+ * chunk that receives the first token generated after the last rebuild (tokens at the rebuild /
+ * chunk_size); chunk c >= base_chunk owns entry n_sel - 1 - (c - base_chunk) of every KV head's list
+ * from the moment its first token exists (the list is ordered by decreasing importance, so its tail
+ * holds the least important chunks).  The call admits chunks first_new_chunk .. first_new_chunk +
+ * n_new_chunks - 1, in that order, per KV head:
+ *   - c is not listed: it replaces the entry at its position (that chunk is evicted);
+ *   - c is already listed among the non-sink entries (the partly filled last chunk, if the rebuild
+ *     selected it; or c was admitted before): it trades places with the entry at its position and
+ *     nothing is evicted; admitting a chunk again is therefore harmless;
+ *   - c is one of the sink entries: nothing changes.
+ * A list must never hold a chunk twice (ts_partial_kv_attn would count its keys twice in the
+ * softmax); ts_topk_chunks writes duplicate-free lists and this call keeps them so.  Call it for the
+ * chunks that received tokens, before the next drafting pass, so that every generated token is
+ * visible to it; ts_partial_kv_attn clips a partly filled chunk to the cache's n_tokens.
  *   chunk_idx  device int32 [n_kv_heads][n_sel], as written by ts_topk_chunks (updated in place)
- * Errors: n_new_chunks < 0 or > n_sel - n_sink_chunks (then a rebuild is due instead).
+ * Errors (TS_ERR_SHAPE): first_new_chunk < base_chunk, n_new_chunks < 0, or first_new_chunk +
+ * n_new_chunks - base_chunk > n_sel - n_sink_chunks (the new chunks would reach the sink: a rebuild
+ * is due instead, which ts_refresh_due reports when it is given the rebuild size rounded down to a
+ * chunk boundary, base_chunk * chunk_size).
  */
-int ts_chunk_list_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int n_sink_chunks,
+int ts_chunk_list_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int n_sink_chunks, int base_chunk,
                         int first_new_chunk, int n_new_chunks, void *stream);
 
 /*

@@ -68,7 +68,7 @@ def load_library():
     i32p = ctypes.POINTER(ctypes.c_int32)
     lib.ts_append_accepted.argtypes = [kvp, vp, vp, ci, i32p, ci, vp]
     lib.ts_refresh_due.argtypes = [i64, i64, i64, i64]
-    lib.ts_chunk_list_admit.argtypes = [vp, ci, ci, ci, ci, ci, vp]
+    lib.ts_chunk_list_admit.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp]
     lib.ts_gather_chunks.argtypes = [kvp, vp, ci, ci, vp, vp, vp]
     lib.ts_chunk_key_sums.argtypes = [kvp, ci, i64, i64, vp, i64, vp]
     lib.ts_chunk_scores_from_sums.argtypes = [vp, i64, ci, i64, vp, ci, ci, cf, vp, vp]
@@ -259,12 +259,15 @@ def refresh_due(n_tokens: int, n_tokens_at_refresh: int, budget_tokens: int, sin
     return bool(rc)
 
 
-def chunk_list_admit(chunk_idx: torch.Tensor, n_sink_chunks: int, first_new_chunk: int, n_new_chunks: int) -> torch.Tensor:
-    """chunk_idx int32 [Hkv,n_sel] (contiguous, updated in place)."""
+def chunk_list_admit(chunk_idx: torch.Tensor, n_sink_chunks: int, base_chunk: int, first_new_chunk: int,
+                     n_new_chunks: int) -> torch.Tensor:
+    """chunk_idx int32 [Hkv,n_sel] (contiguous, updated in place); base_chunk: the chunk that received the
+    first token after the last rebuild."""
     if not chunk_idx.is_contiguous():
         raise ValueError("chunk_idx must be contiguous")
     _check(load_library().ts_chunk_list_admit(chunk_idx.data_ptr(), chunk_idx.shape[0], chunk_idx.shape[1],
-                                              int(n_sink_chunks), int(first_new_chunk), int(n_new_chunks), _stream()),
+                                              int(n_sink_chunks), int(base_chunk), int(first_new_chunk),
+                                              int(n_new_chunks), _stream()),
            "ts_chunk_list_admit")
     return chunk_idx
 

@@ -24,10 +24,32 @@ __global__ void __launch_bounds__(64) append_kernel(const AppendParams p)
 }
 
 // ---- admit new chunks at the tail of the chunk lists --------------------------------------------
-__global__ void __launch_bounds__(64) admit_kernel(int32_t *chunk_idx, int n_sel, int first_new_chunk, int n_new)
+// One workgroup per KV head.  New chunk c owns position n_sel - 1 - (c - base_chunk).  The chunks are
+// taken one after the other (a swap may move an entry that a later chunk then evicts); for each, all
+// threads look for c in the list and thread 0 applies the one change.
+__global__ void __launch_bounds__(256) admit_kernel(int32_t *chunk_idx, int n_sel, int n_sink, int base_chunk,
+                                                    int first_new_chunk, int n_new)
 {
-    const int h = blockIdx.x;
-    for (int i = threadIdx.x; i < n_new; i += 64) chunk_idx[(int64_t)h * n_sel + (n_sel - 1 - i)] = first_new_chunk + i;
+    __shared__ int found_at;
+    int32_t *list = chunk_idx + (int64_t)blockIdx.x * n_sel;
+    for (int c = first_new_chunk; c < first_new_chunk + n_new; ++c) {
+        if (threadIdx.x == 0) found_at = -1;
+        __syncthreads();
+        for (int j = threadIdx.x; j < n_sel; j += 256)
+            if (list[j] == c) found_at = j;          // the list holds no chunk twice: at most one writer
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const int pos = n_sel - 1 - (c - base_chunk);
+            const int j = found_at;
+            if (j < 0) {
+                list[pos] = c;                        // evicts the least important entry still listed
+            } else if (j >= n_sink && j != pos) {     // already listed: trade places, nothing is evicted
+                list[j] = list[pos];
+                list[pos] = c;
+            }
+        }
+        __syncthreads();
+    }
 }
 
 // ---- copy the listed chunks into contiguous buffers ----------------------------------------------
@@ -156,9 +178,10 @@ hipError_t launch_append(const AppendParams &p, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int first_new_chunk, int n_new, hipStream_t stream)
+hipError_t launch_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int n_sink, int base_chunk, int first_new_chunk, int n_new,
+                        hipStream_t stream)
 {
-    hipLaunchKernelGGL(admit_kernel, dim3(n_kv_heads), dim3(64), 0, stream, chunk_idx, n_sel, first_new_chunk, n_new);
+    hipLaunchKernelGGL(admit_kernel, dim3(n_kv_heads), dim3(256), 0, stream, chunk_idx, n_sel, n_sink, base_chunk, first_new_chunk, n_new);
     return hipGetLastError();
 }
 

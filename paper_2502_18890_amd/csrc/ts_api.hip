@@ -454,15 +454,17 @@ int ts_refresh_due(int64_t n_tokens, int64_t n_tokens_at_refresh, int64_t budget
     return (n_tokens - n_tokens_at_refresh) > (budget_tokens - sink_tokens) ? 1 : 0;
 }
 
-int ts_chunk_list_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int n_sink_chunks,
+int ts_chunk_list_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int n_sink_chunks, int base_chunk,
                         int first_new_chunk, int n_new_chunks, void *stream)
 {
     if (!chunk_idx) return TS_ERR_NULL;
-    if (n_kv_heads < 1 || n_sel < 1 || n_sink_chunks < 0 || n_sink_chunks > n_sel || first_new_chunk < 0) return TS_ERR_SHAPE;
-    if (n_new_chunks < 0 || n_new_chunks > n_sel - n_sink_chunks) return TS_ERR_SHAPE;
+    if (n_kv_heads < 1 || n_sel < 1 || n_sink_chunks < 0 || n_sink_chunks > n_sel || base_chunk < 0) return TS_ERR_SHAPE;
+    if (n_kv_heads > 65535) return TS_ERR_UNSUPPORTED;
+    if (n_new_chunks < 0 || first_new_chunk < base_chunk) return TS_ERR_SHAPE;
     if ((int64_t)first_new_chunk + n_new_chunks > 0x7fffffffLL) return TS_ERR_SHAPE;
+    if ((int64_t)first_new_chunk + n_new_chunks - base_chunk > n_sel - n_sink_chunks) return TS_ERR_SHAPE;   // a rebuild is due instead
     if (n_new_chunks == 0) return TS_OK;
-    return ts::launch_admit(chunk_idx, n_kv_heads, n_sel, first_new_chunk, n_new_chunks,
+    return ts::launch_admit(chunk_idx, n_kv_heads, n_sel, n_sink_chunks, base_chunk, first_new_chunk, n_new_chunks,
                             static_cast<hipStream_t>(stream)) == hipSuccess ? TS_OK : TS_ERR_HIP;
 }
 

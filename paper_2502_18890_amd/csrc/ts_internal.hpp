@@ -145,7 +145,8 @@ struct AppendParams {
     int32_t accepted[kMaxTree];
 };
 hipError_t launch_append(const AppendParams &p, hipStream_t stream);
-hipError_t launch_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int first_new_chunk, int n_new, hipStream_t stream);
+hipError_t launch_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int n_sink, int base_chunk, int first_new_chunk, int n_new,
+                        hipStream_t stream);
 
 struct GatherParams {
     const uint16_t *k, *v;

@@ -186,10 +186,13 @@ def test_cache_maintenance_calls_reject_bad_arguments(lib, binding):
     assert rd(100, 50, 64, 16) == 1 and rd(98, 50, 64, 16) == 0 and rd(99, 50, 64, 16) == 1 and rd(50, 50, 64, 16) == 0
     assert rd(-1, 0, 64, 16) == TS_ERR_SHAPE and rd(10, 11, 64, 16) == TS_ERR_SHAPE and rd(10, 5, 8, 16) == TS_ERR_SHAPE
 
-    ad = lambda idx=0x5000, hkv=2, n_sel=9, sink=1, first=40, n_new=2: lib.ts_chunk_list_admit(idx, hkv, n_sel, sink, first, n_new, None)
+    ad = lambda idx=0x5000, hkv=2, n_sel=9, sink=1, base=40, first=40, n_new=2: lib.ts_chunk_list_admit(
+        idx, hkv, n_sel, sink, base, first, n_new, None)
     assert ad(idx=None) == TS_ERR_NULL
-    assert ad(n_new=9) == TS_ERR_SHAPE and ad(n_new=-1) == TS_ERR_SHAPE and ad(first=-3) == TS_ERR_SHAPE
-    assert ad(sink=10) == TS_ERR_SHAPE and ad(n_new=0) == 0          # nothing to do: no launch
+    assert ad(n_new=9) == TS_ERR_SHAPE and ad(n_new=-1) == TS_ERR_SHAPE and ad(base=-3, first=-3) == TS_ERR_SHAPE
+    assert ad(first=39) == TS_ERR_SHAPE                              # a chunk from before the rebuild
+    assert ad(first=47, n_new=2) == TS_ERR_SHAPE                     # would reach the sink: rebuild instead
+    assert ad(sink=10) == TS_ERR_SHAPE and ad(n_new=0) == 0 and ad(first=48, n_new=0) == 0   # nothing to do: no launch
 
     ga = lambda view=None, idx=0x5000, n_sel=3, chunk=64, ko=0x8000, vo=0x9000: lib.ts_gather_chunks(
         ctypes.byref(view if view is not None else _view(binding)), idx, n_sel, chunk, ko, vo, None)

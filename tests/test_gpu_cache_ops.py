@@ -73,13 +73,32 @@ def test_then_verification_sees_the_appended_tokens(ts):
     assert_close(out.cpu().numpy(), ref, "verify after append")
 
 
-@pytest.mark.parametrize("hkv,n_sel,n_sink,first,n_new", [(2, 9, 1, 40, 2), (32, 65, 1, 1563, 3), (3, 5, 0, 7, 5), (4, 130, 2, 10, 128)])
-def test_chunk_list_admit_is_exact(ts, hkv, n_sel, n_sink, first, n_new):
+@pytest.mark.parametrize("hkv,n_sel,n_sink,base,first,n_new", [(2, 9, 1, 40, 40, 2), (32, 65, 1, 1562, 1563, 3), (3, 5, 0, 7, 7, 5),
+                                                               (4, 130, 2, 10, 10, 128), (4, 600, 1, 900, 950, 40), (1, 4, 1, 5, 6, 0)])
+def test_chunk_list_admit_is_exact(ts, hkv, n_sel, n_sink, base, first, n_new):
+    """Lists without duplicates (as ts_topk_chunks writes them), some of which already hold one or two of
+    the chunks being admitted, at a non-sink position or among the sink entries."""
     import torch
     rng = np.random.default_rng(34)
-    idx = rng.integers(0, 1000, size=(hkv, n_sel)).astype(np.int32)
-    got = ts.chunk_list_admit(torch.from_numpy(idx).cuda(), n_sink, first, n_new)
-    np.testing.assert_array_equal(got.cpu().numpy(), C.chunk_list_admit(idx, n_sink, first, n_new))
+    idx = np.stack([rng.permutation(np.arange(0, first + n_new + 50))[:n_sel] for _ in range(hkv)]).astype(np.int32)
+    for h in range(hkv):
+        assert len(set(idx[h].tolist())) == n_sel
+    got = ts.chunk_list_admit(torch.from_numpy(idx).cuda(), n_sink, base, first, n_new)
+    ref = C.chunk_list_admit(idx, n_sink, base, first, n_new)
+    np.testing.assert_array_equal(got.cpu().numpy(), ref)
+    for h in range(hkv):
+        assert len(set(ref[h].tolist())) == n_sel
+    # a second, overlapping call (later tokens of the same chunks) changes nothing
+    again = ts.chunk_list_admit(got.clone(), n_sink, base, first, n_new)
+    np.testing.assert_array_equal(again.cpu().numpy(), ref)
+
+
+def test_chunk_list_admit_already_listed_cases(ts):
+    import torch
+    idx = np.array([[0, 7, 12, 9, 5], [0, 2, 8, 4, 12], [12, 3, 8, 4, 6], [0, 13, 12, 4, 6]], dtype=np.int32)
+    for n_new in (1, 2):
+        got = ts.chunk_list_admit(torch.from_numpy(idx).cuda(), 1, 12, 12, n_new).cpu().numpy()
+        np.testing.assert_array_equal(got, C.chunk_list_admit(idx, 1, 12, 12, n_new))
 
 
 @pytest.mark.parametrize("hkv,n,chunk,n_sel", [(2, 300, 32, 3), (8, 4096, 64, 9), (1, 17, 16, 2), (4, 1000, 128, 5)])

@@ -348,8 +348,8 @@ def test_verify_kernel_variants(ts, variant, hq, hkv, n, t):
 def test_verify_values_outside_half_range(ts, variant, kind, hq, hkv, n, t):
     """For more than 32 rows per KV head the weights meet V in fp16 when V fits.  Values that do
     not fit -- magnitudes of 65520 and more, or tokens whose values all lie below 2^-14 -- must
-    be caught and take the bf16 route: the result still matches the oracle, relative to the size
-    of the output."""
+    be caught and take the bf16 route: the result still matches the oracle ("tiny": at the bar as it
+    stands; "huge": relative to the size of the output, see below)."""
     if kind == "tiny":
         c = _case(31, hq, hkv, n, t, vscale=2.0 ** -30)
     else:
@@ -366,8 +366,15 @@ def test_verify_values_outside_half_range(ts, variant, kind, hq, hkv, n, t):
         out, lse, ref, rlse = _verify_both(ts, c, parent)
     finally:
         ts.tune_set("verify_variant", 0)
-    size = max(1.0, float(np.max(np.abs(ref))))
-    assert_close(out / size, ref / size, "verify out, %s values" % kind)
+    if kind == "tiny":
+        assert_close(out, ref, "verify out, tiny values")          # the bar as it stands (absolute and relative L2)
+    else:
+        # Stated exception to the absolute bar: with planted values of 1e30 the outputs themselves reach ~1e27,
+        # where fp32 has an absolute resolution of ~1e20.  Both sides are divided by the largest reference
+        # magnitude before the bar is applied, i.e. max-abs is taken relative to the size of the output.
+        size = float(np.max(np.abs(ref)))
+        assert size > 1.0e20
+        assert_close(out / size, ref / size, "verify out, huge values")
     assert_close(lse, rlse, "verify lse, %s values" % kind)
 
 

@@ -1,9 +1,10 @@
 """GPU parity of the penalized probabilities and the pool sampler (through the C ABI) against the
-numpy oracle.  Probabilities: the floating-point bar.  Sampled tokens and pool thresholds are
-decisions that floating point takes: the oracle is given the GPU's own fp32 probabilities and takes
-them in fp32 too; a draw is compared exactly unless the oracle says it was not decisive (the target
-within 1e-5 of a step of the cumulative distribution), in which case the neighbouring pool token is
-accepted as well."""
+numpy oracle.  Probabilities: the floating-point bar.  Pool thresholds and sampled tokens are
+decisions that floating point takes.  The oracle (fp64) is given the GPU's own fp32 probabilities; the
+test states, from the oracle's side, which thresholds are admissible given fp32 rounding and requires
+the GPU's to be one of them; the draw is then compared exactly with the oracle's draw from the pool of
+that threshold, unless the oracle says the draw was not decisive (the target within 1e-5 of a step of
+the cumulative distribution), in which case the neighbouring pool token is accepted as well."""
 import numpy as np
 import pytest
 
@@ -54,6 +55,43 @@ def test_penalized_probs_peaked_and_flat_rows(ts):
     assert_close(got, O.penalized_probs(lg, window, 1.0, 1.2), "penalized probs, peaked/flat")
 
 
+def _pool_mass(p64, tau):
+    return float(p64[p64 >= tau].sum())
+
+
+def _assert_threshold_admissible(p_row, method, param, param2, thr):
+    """The threshold is a decision floating point takes.  The admissible thresholds are stated here from the
+    oracle's side (fp64 on the row's exact values), and the GPU's must be one of them:
+      full   tau = 0.
+      min-p  tau = p_base * p_max up to fp32 rounding; the pool may differ from the oracle's only in tokens whose
+             probability lies within that rounding of the threshold.
+      top-p  tau is one of the row's values, its pool holds mass >= p - 1e-6, and the pool of the next larger value
+             (the same pool without the tokens tied at tau) holds mass < p + 1e-6: the smallest pool that reaches p,
+             where masses within 1e-6 of p count as either side (the kernel adds masses in units of 2^-40, each
+             probability within half a unit: 7e-8 over a vocabulary of 152K).
+      eta    tau = min(epsilon, alpha * exp(-entropy)) to 2e-5 relative (an fp32 sum over the vocabulary); the pool may
+             differ from the oracle's only in tokens within that distance of the threshold."""
+    p64 = np.asarray(p_row, dtype=np.float64)
+    thr = float(thr)
+    tau = O.pool_threshold(p_row, method, float(np.float32(param)), float(np.float32(param2)))
+    if method == O.FULL:
+        assert thr == 0.0
+        return
+    if method == O.TOP_P:
+        if thr == tau:
+            return
+        assert np.any(p64 == thr), ("top-p threshold is not a probability of the row", thr)
+        want = float(np.float32(param))
+        assert _pool_mass(p64, thr) >= want - 1e-6, ("top-p pool too small", thr, _pool_mass(p64, thr), want)
+        larger = p64[p64 > thr]
+        assert larger.size == 0 or _pool_mass(p64, float(larger.min())) < want + 1e-6, ("top-p pool not minimal", thr, tau)
+        return
+    rel = 1e-6 if method == O.MIN_P else 2e-5
+    assert abs(thr - tau) <= rel * tau, (method, thr, tau)
+    differs = (p64 >= thr) != (p64 >= tau)
+    assert np.all(np.abs(p64[differs] - tau) <= rel * tau), ("pool differs away from the threshold", method, thr, tau)
+
+
 def _check_draws(ts, probs_gpu, method, param, u, param2=0.0):
     import torch
     p = probs_gpu.cpu().numpy()
@@ -61,26 +99,14 @@ def _check_draws(ts, probs_gpu, method, param, u, param2=0.0):
     tok, thr, mass = tok.cpu().numpy(), thr.cpu().numpy(), mass.cpu().numpy()
     n_ambiguous = 0
     for r in range(p.shape[0]):
-        tau = O.pool_threshold(p[r], method, param, param2)
-        if method == O.ETA:
-            # eta comes out of an fp32 entropy sum: equal to the oracle's to rounding, not bit for bit
-            assert abs(float(thr[r]) - float(tau)) <= 2e-5 * float(tau), (r, thr[r], tau)
-            tau = thr[r]
-        if method == O.TOP_P:
-            # the cut itself is a floating-point decision: accept the neighbouring thresholds when the mass
-            # at the cut is within 1e-5 of param
-            order = np.sort(p[r].astype(np.float64))[::-1]
-            cum = np.cumsum(order)
-            near = np.abs(cum - param) < 1e-5
-            if near.any() and thr[r] != tau:   # e.g. param = 1.0: the whole row's mass is 1 only up to rounding
-                tau = thr[r]
-        assert thr[r] == tau, (r, thr[r], tau)
-        ref_tok, ref_mass, margin = O.sample(np.where(p[r] >= tau, p[r], 0).astype(np.float32), O.FULL, 0.0, u[r])
+        _assert_threshold_admissible(p[r], method, param, param2, thr[r])
+        # the draw, against the pool the oracle derives from that (admissible) threshold
+        ref_tok, ref_mass, margin = O.sample_from_pool(p[r], float(thr[r]), u[r])
         assert abs(mass[r] - ref_mass) <= 1e-5 * max(ref_mass, 1e-30)
-        assert p[r, tok[r]] >= tau and p[r, tok[r]] > 0
+        assert p[r, tok[r]] >= thr[r] and p[r, tok[r]] > 0
         if tok[r] != ref_tok:
             assert margin < 1e-5, (r, tok[r], ref_tok, margin)
-            pool_ids = np.nonzero(p[r] >= tau)[0]
+            pool_ids = np.nonzero(p[r] >= thr[r])[0]
             assert abs(int(np.searchsorted(pool_ids, tok[r])) - int(np.searchsorted(pool_ids, ref_tok))) == 1
             n_ambiguous += 1
     assert n_ambiguous <= max(1, p.shape[0] // 10)
