@@ -6,8 +6,9 @@
  *
  * General conventions
  *   - Every pointer is a DEVICE pointer unless its comment says HOST.  The caller owns all
- *     buffers, including the workspace; the library keeps no state between calls and never
- *     allocates or frees device memory.
+ *     buffers, including the workspace; the library never allocates or frees device memory and
+ *     keeps no state between calls other than the overrides of ts_tune_set and, per device, its
+ *     number of compute units (read once).
  *   - bf16 arrays are passed as `const void*` (2-byte elements, IEEE bfloat16 bit patterns).
  *     Outputs are fp32.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
@@ -131,8 +132,8 @@ int ts_topk_chunks(const float *scores, int n_kv_heads, int n_chunks, int n_sink
  *   out        fp32 [n_q_heads][128]
  *   lse        fp32 [n_q_heads], natural-log sum of exponentials of the scaled logits; nullable
  *   workspace  >= ts_workspace_bytes(TS_OP_PARTIAL_ATTN, ...) bytes, 256-byte aligned
- * chunk_size: multiple of 16, 16..1024.  scale must be positive and finite (TS_ERR_UNSUPPORTED
- * otherwise).  Errors as above plus n_sel < 1.
+ * chunk_size: multiple of 16, 16..1024.  scale must be positive and below 2e38, so that scale * log2(e)
+ * is finite (TS_ERR_UNSUPPORTED otherwise).  Errors as above plus n_sel < 1.
  */
 int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
                        const int32_t *chunk_idx, int n_sel, int chunk_size, float scale,
@@ -152,7 +153,7 @@ int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
  *   lse             fp32 [n_tree][n_q_heads]; nullable
  *   workspace       >= ts_workspace_bytes(TS_OP_TREE_VERIFY, ...) bytes, 256-byte aligned
  * n_tree: 1..TS_MAX_TREE.  kv->n_tokens may be 0 (then kv->k, kv->v may be NULL).  scale must be
- * positive and finite (TS_ERR_UNSUPPORTED otherwise).
+ * positive and below 2e38 (TS_ERR_UNSUPPORTED otherwise).
  * Errors: TS_ERR_TREE for a malformed parent array; the others as above.
  */
 int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
@@ -161,12 +162,14 @@ int ts_tree_verify_attn(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
                         size_t workspace_bytes, void *stream);
 
 /*
- * The same verification pass, which also leaves the chunk importance scores of the cache (Sec. 3.3:
- * the scores are recalculated from the query-key products of the forward pass over the full
- * cache; Eq. 2) for the query of tree node 0, the token the iteration started from:
+ * The same verification pass, which also leaves chunk importance scores of the cache (Eq. 2) for the
+ * query of tree node 0:
  *   scores[h][c] = scale * mean over the tokens t of chunk c of sum_{j in group h} q_tree[0][j] . K[h][t],
  * i.e. what ts_chunk_scores returns for q = q_tree[0], at no extra pass over the keys: the rows of node 0
- * hold these products anyway.
+ * hold these products anyway.  Sec. 3.3 says that the scores are recomputed from query-key products; it
+ * does not say of which forward pass or of which query.  Taking the verification pass and the query of
+ * tree node 0 (the token the iteration starts from) is this library's reading; a caller that ranks the
+ * cache with another query uses ts_chunk_scores or ts_chunk_scores_from_sums.
  *   scores      fp32 [n_kv_heads][ceil(N / chunk_size)]  (written; valid when the stream reaches the call)
  *   chunk_size  multiple of 32, 32..1024 (TS_ERR_UNSUPPORTED otherwise)
  *   workspace   >= ts_workspace_bytes(TS_OP_TREE_VERIFY_SCORED, ...) bytes, 256-byte aligned
@@ -307,13 +310,26 @@ int ts_sample_tokens(const float *probs, int n_rows, int64_t vocab, int method, 
 /*
  * Tuning hook (not needed for correct results): overrides a launch-geometry choice until
  * reset with value 0.  Names: "verify_splits" (number of cache splits per KV head);
- * "verify_variant" (1..3: alternative kernel shapes of the verification pass);
- * "verify_stage" (1: ts_tree_verify_attn enqueues only its split kernel, 2: only its merge
- * kernel -- for timing one kernel alone; outputs are then not meaningful).  Returns TS_OK, or
- * TS_ERR_UNSUPPORTED for an unknown name or a value the kernels cannot run.  The same
- * setting is seen by ts_workspace_bytes.  Not thread-safe against concurrent calls.
+ * "verify_variant" (1..3: alternative kernel shapes of the verification pass).  Every setting
+ * produces the same results up to rounding order.  Returns TS_OK, or TS_ERR_UNSUPPORTED for an
+ * unknown name or a value the kernels cannot run.  The same setting is seen by ts_workspace_bytes,
+ * so size the workspace after setting it.  This is the only mutable state of the library (process-wide,
+ * atomic words: a concurrent call sees the old or the new value).
  */
 int ts_tune_set(const char *name, int value);
+
+/*
+ * Measurement utility (no passage of the paper): enqueues ONLY the first of the two kernels of
+ * ts_tree_verify_attn -- the one that streams the cache and leaves per-split partial results in the
+ * workspace -- so that it can be timed alone for the roofline figure.  No output is produced (there are no
+ * out / lse arguments); the workspace contents afterwards are scratch.  with_tile_sums != 0 runs the
+ * variant of ts_tree_verify_attn_scored (size the workspace for TS_OP_TREE_VERIFY_SCORED then), else
+ * that of ts_tree_verify_attn.  Arguments and errors otherwise as for those calls.
+ */
+int ts_bench_verify_split_kernel(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
+                                 const void *k_tree, const void *v_tree, const int32_t *parent,
+                                 int n_tree, float scale, int with_tile_sums, void *workspace,
+                                 size_t workspace_bytes, void *stream);
 
 /*
  * Measurement utility (no passage of the paper): enqueues a kernel that reads `bytes` bytes at

@@ -66,6 +66,7 @@ def load_library():
     lib.ts_tree_verify_attn_scored.argtypes = [kvp, vp, ci, vp, vp, ctypes.POINTER(ctypes.c_int32), ci, cf, ci, vp,
                                                vp, vp, vp, ctypes.c_size_t, vp]
     i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.ts_bench_verify_split_kernel.argtypes = [kvp, vp, ci, vp, vp, i32p, ci, cf, ci, vp, ctypes.c_size_t, vp]
     lib.ts_append_accepted.argtypes = [kvp, vp, vp, ci, i32p, ci, vp]
     lib.ts_refresh_due.argtypes = [i64, i64, i64, i64]
     lib.ts_chunk_list_admit.argtypes = [vp, ci, ci, ci, ci, ci, ci, vp]
@@ -79,7 +80,7 @@ def load_library():
     lib.ts_penalized_probs.restype = ci
     lib.ts_sample_tokens.restype = ci
     lib.ts_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp, vp]
-    for name in ("ts_stream_read_probe", "ts_tune_set", "ts_chunk_scores", "ts_topk_chunks", "ts_partial_kv_attn",
+    for name in ("ts_bench_verify_split_kernel", "ts_stream_read_probe", "ts_tune_set", "ts_chunk_scores", "ts_topk_chunks", "ts_partial_kv_attn",
                  "ts_tree_verify_attn", "ts_tree_verify_attn_scored", "ts_append_accepted", "ts_refresh_due", "ts_chunk_list_admit",
                  "ts_gather_chunks", "ts_chunk_key_sums", "ts_chunk_scores_from_sums"):
         getattr(lib, name).restype = ci
@@ -232,6 +233,19 @@ def tree_verify_attn(q_tree: torch.Tensor, k: Optional[torch.Tensor], v: Optiona
                                    par, t, float(scale), out.data_ptr(), lse_ptr, workspace.data_ptr(),
                                    workspace.numel(), _stream()), "ts_tree_verify_attn")
     return (out, lse) if lse is not None else out
+
+
+def bench_verify_split_kernel(q_tree: torch.Tensor, k: torch.Tensor, v: torch.Tensor, k_tree: torch.Tensor,
+                              v_tree: torch.Tensor, parent: Sequence[int], scale: float, workspace: torch.Tensor,
+                              with_tile_sums: bool = False) -> None:
+    """Measurement utility: enqueues only the cache-streaming kernel of the verification pass (no output)."""
+    lib = load_library()
+    t, hq = q_tree.shape[0], q_tree.shape[1]
+    kv = _view(k, v, k_tree.shape[1])
+    par = (ctypes.c_int32 * len(parent))(*[int(x) for x in parent])
+    _check(lib.ts_bench_verify_split_kernel(ctypes.byref(kv), q_tree.data_ptr(), hq, k_tree.data_ptr(), v_tree.data_ptr(), par, t,
+                                            float(scale), int(bool(with_tile_sums)), workspace.data_ptr(), workspace.numel(),
+                                            _stream()), "ts_bench_verify_split_kernel")
 
 
 # ---- cache maintenance -----------------------------------------------------------------------

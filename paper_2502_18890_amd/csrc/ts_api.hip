@@ -7,13 +7,30 @@
 
 namespace {
 
-constexpr int kNumCUs = 256;   // MI355X
-
+// The only state the library keeps: launch-geometry overrides (ts_tune_set) and, per device, the
+// number of compute units, read once.  Both are plain atomics: a reader sees the old or the new value.
 struct Tuning {
-    int verify_splits = 0;     // 0 = heuristic
-    int verify_stage = 0;      // 0 = both kernels, 1 = split kernel only, 2 = merge kernel only
-    int verify_variant = 0;    // 0 = default kernel shapes; 1, 2 = alternatives (see verify_shape)
+    std::atomic<int> verify_splits{0};     // 0 = heuristic
+    std::atomic<int> verify_variant{0};    // 0 = default kernel shapes; 1..3 = alternatives (see verify_shape)
 } g_tune;
+
+// Compute units of the current device (256 on a whole MI355X, fewer on a partitioned one): the split
+// heuristic fills exactly one resident round of workgroups.  Falls back to 256 if the query fails.
+int device_cus()
+{
+    constexpr int kMaxDev = 64;
+    static std::atomic<int> cached[kMaxDev];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (dev >= 0 && dev < kMaxDev) {
+        const int c = cached[dev].load(std::memory_order_relaxed);
+        if (c > 0) return c;
+    }
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    if (dev >= 0 && dev < kMaxDev) cached[dev].store(cus, std::memory_order_relaxed);
+    return cus;
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -60,7 +77,7 @@ bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, bo
     const int group = n_q_heads / n_kv_heads;
     pl->n_rows = group * n_tree;
     pl->n_rows_pad = (pl->n_rows + 15) / 16 * 16;
-    if (!ts::verify_shape(pl->n_rows, n_kv_heads, g_tune.verify_variant, &pl->shape)) return false;
+    if (!ts::verify_shape(pl->n_rows, n_kv_heads, g_tune.verify_variant.load(std::memory_order_relaxed), &pl->shape)) return false;
     int n_split = 0;
     int64_t split_len = 32;
     if (n_tokens > 0) {
@@ -69,10 +86,11 @@ bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, bo
         // - 1: the tree split.  Not for the two-wavefront 16x16x32 kernel: its tree workgroups are over in a
         // few microseconds, so letting them (and the cache workgroups that then start late) run in slots that
         // free up early costs less than leaving one slot in 32 idle for the whole pass (257 vs 260 us at 100K).
-        int64_t want = (int64_t)kNumCUs * pl->shape.wg_per_cu / per_split - (pl->shape.kernel_id == ts::kNarrow_32 ? 0 : 1);
+        int64_t want = (int64_t)device_cus() * pl->shape.wg_per_cu / per_split - (pl->shape.kernel_id == ts::kNarrow_32 ? 0 : 1);
         const int64_t cap_traffic = (n_tokens * 512 / 4) / ((int64_t)pl->n_rows_pad * 520) + 1;  // partials <= 1/4 of K/V
         if (want > cap_traffic) want = cap_traffic;
-        if (g_tune.verify_splits > 0) want = g_tune.verify_splits;
+        const int forced = g_tune.verify_splits.load(std::memory_order_relaxed);
+        if (forced > 0) want = forced;
         const int64_t max_split = (n_tokens + 31) / 32;
         if (want > max_split) want = max_split;
         if (want < 1) want = 1;
@@ -105,8 +123,9 @@ void plan_partial(int n_q_heads, int n_kv_heads, int n_sel, int chunk_size, Part
     pl->bytes = pl->ml_offset + round_up(rows_total * 2 * sizeof(float), 256);
 }
 
-// the attention kernels take row maxima before scaling the logits
-bool scale_ok(float scale) { return scale > 0.f && scale < 3.0e38f; }
+// the attention kernels take row maxima before scaling the logits, and work with scale * log2(e), which
+// must stay finite
+bool scale_ok(float scale) { return scale > 0.f && scale < 2.0e38f; }
 
 bool partial_chunk_ok(int chunk_size) { return chunk_size >= 16 && chunk_size <= 1024 && chunk_size % 16 == 0; }
 
@@ -174,7 +193,7 @@ const char *ts_strerror(int status)
     }
 }
 
-int ts_version(void) { return 200; }
+int ts_version(void) { return 210; }
 
 int ts_tune_set(const char *name, int value)
 {
@@ -186,11 +205,6 @@ int ts_tune_set(const char *name, int value)
     if (strcmp(name, "verify_variant") == 0) {
         if (value > 3) return TS_ERR_UNSUPPORTED;
         g_tune.verify_variant = value;
-        return TS_OK;
-    }
-    if (strcmp(name, "verify_stage") == 0) {
-        if (value > 2) return TS_ERR_UNSUPPORTED;
-        g_tune.verify_stage = value;
         return TS_OK;
     }
     return TS_ERR_UNSUPPORTED;
@@ -314,23 +328,25 @@ int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
 }
 
 // ts_tree_verify_attn, and with scores != nullptr ts_tree_verify_attn_scored
+// split_only: enqueue the split kernel alone (ts_bench_verify_split_kernel); out is then unused
 static int verify_call(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
                        const void *k_tree, const void *v_tree, const int32_t *parent,
                        int n_tree, float scale, int chunk_size, float *scores, float *out, float *lse,
-                       void *workspace, size_t workspace_bytes, void *stream)
+                       void *workspace, size_t workspace_bytes, void *stream, bool split_only = false, bool split_only_sums = false)
 {
+    const bool scored = scores != nullptr || split_only_sums;   // the split kernel also leaves the per-tile logit sums
     int rc = check_view(kv, true, true);
     if (rc != TS_OK) return rc;
-    if (!q_tree || !k_tree || !v_tree || !parent || !out) return TS_ERR_NULL;
+    if (!q_tree || !k_tree || !v_tree || !parent || (!out && !split_only)) return TS_ERR_NULL;
     int group = 0;
     if ((rc = check_heads(n_q_heads, kv->n_kv_heads, &group)) != TS_OK) return rc;
     if (n_tree < 1) return TS_ERR_SHAPE;
     if (n_tree > TS_MAX_TREE || !scale_ok(scale)) return TS_ERR_UNSUPPORTED;
     for (int i = 0; i < n_tree; ++i)
         if (parent[i] < -1 || parent[i] >= i) return TS_ERR_TREE;
-    if (!aligned16(q_tree) || !aligned16(k_tree) || !aligned16(v_tree) || !aligned16(out)) return TS_ERR_ALIGN;
+    if (!aligned16(q_tree) || !aligned16(k_tree) || !aligned16(v_tree) || (out && !aligned16(out))) return TS_ERR_ALIGN;
     VerifyPlan pl;
-    if (!plan_verify(n_q_heads, kv->n_kv_heads, kv->n_tokens, n_tree, scores != nullptr, &pl)) return TS_ERR_UNSUPPORTED;
+    if (!plan_verify(n_q_heads, kv->n_kv_heads, kv->n_tokens, n_tree, scored, &pl)) return TS_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < pl.bytes || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return TS_ERR_WORKSPACE;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -342,7 +358,7 @@ static int verify_call(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
     p.v_tree = static_cast<const uint16_t *>(v_tree);
     p.ws_o = reinterpret_cast<float *>(workspace);
     p.ws_ml = reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.ml_offset);
-    p.tile_sums = scores ? reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.tile_offset) : nullptr;
+    p.tile_sums = scored ? reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + pl.tile_offset) : nullptr;
     p.tile_sums_stride = pl.n_tiles;
     p.stride_head = kv->stride_head;
     p.stride_token = kv->stride_token;
@@ -366,12 +382,12 @@ static int verify_call(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
         }
         p.anc[i][i >> 6] |= 1ull << (i & 63);
     }
-    if (g_tune.verify_stage != 2) {
+    {
         const hipError_t e = pl.shape.kernel_id <= ts::kNarrow_32 ? ts::launch_verify_narrow(p, pl.shape.kernel_id, st)
                                                                   : ts::launch_verify_wide(p, pl.shape.kernel_id, st);
         if (e != hipSuccess) return TS_ERR_HIP;
     }
-    if (g_tune.verify_stage == 1) return TS_OK;
+    if (split_only) return TS_OK;
 
     ts::CombineParams c{};
     c.ws_o = p.ws_o;
@@ -413,6 +429,16 @@ int ts_tree_verify_attn_scored(const ts_kv_view *kv, const void *q_tree, int n_q
     if (chunk_size < 32 || chunk_size > 1024 || chunk_size % 32 != 0) return TS_ERR_UNSUPPORTED;   // whole 32-key tiles
     return verify_call(kv, q_tree, n_q_heads, k_tree, v_tree, parent, n_tree, scale, chunk_size, scores, out, lse, workspace,
                        workspace_bytes, stream);
+}
+
+int ts_bench_verify_split_kernel(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
+                                 const void *k_tree, const void *v_tree, const int32_t *parent,
+                                 int n_tree, float scale, int with_tile_sums, void *workspace,
+                                 size_t workspace_bytes, void *stream)
+{
+    if (with_tile_sums && kv && kv->n_tokens < 1) return TS_ERR_SHAPE;
+    return verify_call(kv, q_tree, n_q_heads, k_tree, v_tree, parent, n_tree, scale, 32, nullptr, nullptr, nullptr, workspace,
+                       workspace_bytes, stream, true, with_tile_sums != 0);
 }
 
 int ts_append_accepted(const ts_kv_view *kv, const void *k_tree, const void *v_tree, int n_tree,

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_function(lib):
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(ts_[a-z_]+)\s*\(", text)))
-    assert names == ["ts_append_accepted", "ts_chunk_key_sums", "ts_chunk_list_admit", "ts_chunk_scores",
+    assert names == ["ts_append_accepted", "ts_bench_verify_split_kernel", "ts_chunk_key_sums", "ts_chunk_list_admit", "ts_chunk_scores",
                      "ts_chunk_scores_from_sums", "ts_gather_chunks", "ts_partial_kv_attn", "ts_penalized_probs",
                      "ts_refresh_due", "ts_sample_tokens", "ts_sampling_workspace_bytes", "ts_stream_read_probe", "ts_strerror",
                      "ts_topk_chunks", "ts_tree_verify_attn", "ts_tree_verify_attn_scored", "ts_tune_set", "ts_version", "ts_workspace_bytes"]
@@ -106,6 +106,7 @@ def test_attention_calls_reject_bad_arguments(lib, binding):
         ws_, wsb, None)
     assert pa(scale=0.0) == TS_ERR_UNSUPPORTED and pa(scale=-1.0) == TS_ERR_UNSUPPORTED
     assert pa(scale=float("inf")) == TS_ERR_UNSUPPORTED and pa(scale=float("nan")) == TS_ERR_UNSUPPORTED
+    assert pa(scale=2.5e38) == TS_ERR_UNSUPPORTED          # scale * log2(e) would overflow to infinity
     assert pa(idx_=None) == TS_ERR_NULL and pa(out_=None) == TS_ERR_NULL and pa(q_=None) == TS_ERR_NULL
     assert pa(view=_view(binding, v=None)) == TS_ERR_NULL
     assert pa(n_sel=0) == TS_ERR_SHAPE
@@ -119,7 +120,7 @@ def test_attention_calls_reject_bad_arguments(lib, binding):
         return lib.ts_tree_verify_attn(ctypes.byref(view if view is not None else _view(binding)), q, hq, kt, 0x7000,
                                        par, len(parent) if parent is not None else 4, scale, out_, None, ws_, wsb, None)
     assert tv([-1, 0], scale=0.0) == TS_ERR_UNSUPPORTED and tv([-1, 0], scale=-0.5) == TS_ERR_UNSUPPORTED
-    assert tv([-1, 0], scale=float("nan")) == TS_ERR_UNSUPPORTED
+    assert tv([-1, 0], scale=float("nan")) == TS_ERR_UNSUPPORTED and tv([-1, 0], scale=2.5e38) == TS_ERR_UNSUPPORTED
     assert tv(None) == TS_ERR_NULL
     assert tv([-1, 0], kt=None) == TS_ERR_NULL
     assert tv([0, 0]) == TS_ERR_TREE            # a node cannot be its own parent
@@ -154,6 +155,8 @@ def test_tune_set(lib):
     assert lib.ts_tune_set(b"no_such_knob", 1) == TS_ERR_UNSUPPORTED
     assert lib.ts_tune_set(b"verify_splits", -1) == TS_ERR_UNSUPPORTED
     assert lib.ts_tune_set(None, 1) == TS_ERR_UNSUPPORTED
+    assert lib.ts_tune_set(b"verify_stage", 1) == TS_ERR_UNSUPPORTED      # no knob may leave a product call without its output
+    assert lib.ts_tune_set(b"verify_variant", 4) == TS_ERR_UNSUPPORTED and lib.ts_tune_set(b"verify_variant", 0) == TS_OK
 
 
 def test_stream_read_probe_rejects_bad_arguments(lib):
