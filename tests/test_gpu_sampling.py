@@ -65,8 +65,8 @@ def _assert_threshold_admissible(p_row, method, param, param2, thr):
       full   tau = 0.
       min-p  tau = p_base * p_max up to fp32 rounding; the pool may differ from the oracle's only in tokens whose
              probability lies within that rounding of the threshold.
-      top-p  tau is one of the row's values, its pool holds mass >= p - 1e-6, and the pool of the next larger value
-             (the same pool without the tokens tied at tau) holds mass < p + 1e-6: the smallest pool that reaches p,
+      top-p  the pool {p >= tau} holds mass >= p - 1e-6 (or is the whole row), and without its least probable members
+             (the tokens tied at its minimum) it holds mass < p + 1e-6: the smallest pool that reaches p,
              where masses within 1e-6 of p count as either side (the kernel adds masses in units of 2^-40, each
              probability within half a unit: 7e-8 over a vocabulary of 152K).
       eta    tau = min(epsilon, alpha * exp(-entropy)) to 2e-5 relative (an fp32 sum over the vocabulary); the pool may
@@ -80,11 +80,13 @@ def _assert_threshold_admissible(p_row, method, param, param2, thr):
     if method == O.TOP_P:
         if thr == tau:
             return
-        assert np.any(p64 == thr), ("top-p threshold is not a probability of the row", thr)
         want = float(np.float32(param))
-        assert _pool_mass(p64, thr) >= want - 1e-6, ("top-p pool too small", thr, _pool_mass(p64, thr), want)
-        larger = p64[p64 > thr]
-        assert larger.size == 0 or _pool_mass(p64, float(larger.min())) < want + 1e-6, ("top-p pool not minimal", thr, tau)
+        pool = p64[p64 >= thr]
+        assert pool.size > 0, ("top-p pool is empty", thr)
+        # it reaches p -- or it is the whole row, when even that falls short of p (p = 1 and a row that sums to 1 - 1e-7)
+        assert float(pool.sum()) >= want - 1e-6 or pool.size == p64.size, ("top-p pool too small", thr, float(pool.sum()), want)
+        # and it is minimal: without its least probable members (all tied at the pool's minimum) it does not reach p
+        assert _pool_mass(p64, float(np.nextafter(pool.min(), np.inf))) < want + 1e-6, ("top-p pool not minimal", thr, tau)
         return
     rel = 1e-6 if method == O.MIN_P else 2e-5
     assert abs(thr - tau) <= rel * tau, (method, thr, tau)
