@@ -51,6 +51,7 @@ typedef enum {
 #define TS_MAX_CHUNKS (1 << 20)  /* chunks per KV head that ts_topk_chunks can rank */
 #define TS_MAX_TOPK 8192      /* chunks per KV head that ts_topk_chunks can select (k) */
 #define TS_MAX_STRIDE_TOKEN (1 << 24) /* largest stride_token, in elements (32 MiB between token rows) */
+#define TS_STATIC_SCRATCH_BYTES (4 << 20) /* fixed scratch of ts_partial_kv_attn_static, per GPU */
 
 /* One layer's KV cache, as the paper's C_full (Alg. 1): n_tokens cached (key, value) pairs
  * for each of n_kv_heads heads.  Element (h, t, x) of K lives at
@@ -139,6 +140,25 @@ int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
                        const int32_t *chunk_idx, int n_sel, int chunk_size, float scale,
                        float *out, float *lse, void *workspace, size_t workspace_bytes,
                        void *stream);
+
+/*
+ * ts_partial_kv_attn for callers that cannot provide (or allocate) a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical results; the split partials go to a fixed array of TS_STATIC_SCRATCH_BYTES bytes that
+ * lives in the library's device image (each GPU the library runs on holds it until the process ends).
+ * The call allocates and frees nothing.  Its first call on a device looks up that device's address
+ * of the array (once; do this outside a graph capture).
+ *   - Shapes whose partials exceed the array return TS_ERR_WORKSPACE and enqueue nothing:
+ *     ts_workspace_bytes(TS_OP_PARTIAL_ATTN, ...) <= TS_STATIC_SCRATCH_BYTES must hold (the five workloads of
+ *     the benchmark need 0.02 to 1.4 MB).
+ *   - Every call on a GPU shares that GPU's array: calls that may overlap on one GPU (different
+ *     streams, or threads) race on it.  Calls on one stream are ordered and safe.  Nothing in the array
+ *     has to start at zero; it keeps the last call's partials.
+ * Errors otherwise as for ts_partial_kv_attn; TS_ERR_UNSUPPORTED for a device index >= 64.
+ */
+int ts_partial_kv_attn_static(const ts_kv_view *kv, const void *q, int n_q_heads,
+                              const int32_t *chunk_idx, int n_sel, int chunk_size, float scale,
+                              float *out, float *lse, void *stream);
 
 /*
  * Verification attention of the draft-token tree over the full cache (Alg. 1, "Parallel

@@ -61,6 +61,8 @@ def load_library():
     lib.ts_chunk_scores.argtypes = [kvp, vp, ci, ci, cf, vp, vp]
     lib.ts_topk_chunks.argtypes = [vp, ci, ci, ci, ci, vp, vp]
     lib.ts_partial_kv_attn.argtypes = [kvp, vp, ci, vp, ci, ci, cf, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.ts_partial_kv_attn_static.argtypes = [kvp, vp, ci, vp, ci, ci, cf, vp, vp, vp]
+    lib.ts_partial_kv_attn_static.restype = ci
     lib.ts_tree_verify_attn.argtypes = [kvp, vp, ci, vp, vp, ctypes.POINTER(ctypes.c_int32), ci, cf,
                                         vp, vp, vp, ctypes.c_size_t, vp]
     lib.ts_tree_verify_attn_scored.argtypes = [kvp, vp, ci, vp, vp, ctypes.POINTER(ctypes.c_int32), ci, cf, ci, vp,
@@ -186,6 +188,21 @@ def partial_kv_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, chunk_idx
                                   int(chunk_size), float(scale), out.data_ptr(),
                                   lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
                                   workspace.numel(), _stream()), "ts_partial_kv_attn")
+    return (out, lse) if lse is not None else out
+
+
+def partial_kv_attn_static(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, chunk_idx: torch.Tensor,
+                           chunk_size: int, scale: float, out: torch.Tensor, lse: Optional[torch.Tensor] = None):
+    """ts_partial_kv_attn_static: as partial_kv_attn, with the library's fixed scratch instead of a
+    workspace.  Nothing is allocated here either: `out` (and `lse`) are the caller's, q and chunk_idx
+    must already be contiguous."""
+    if not q.is_contiguous() or not chunk_idx.is_contiguous():
+        raise ValueError("q and chunk_idx must be contiguous")
+    kv = _view(k, v)
+    _check(load_library().ts_partial_kv_attn_static(ctypes.byref(kv), q.data_ptr(), q.shape[0], chunk_idx.data_ptr(),
+                                                    chunk_idx.shape[1], int(chunk_size), float(scale), out.data_ptr(),
+                                                    lse.data_ptr() if lse is not None else None, _stream()),
+           "ts_partial_kv_attn_static")
     return (out, lse) if lse is not None else out
 
 

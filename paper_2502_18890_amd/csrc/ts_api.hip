@@ -1,6 +1,7 @@
 // C ABI of the library: argument validation, launch-geometry choice, workspace carve-up.
 // All validation happens on the host before anything is enqueued.
 #include <string.h>
+#include <mutex>
 
 #include "../../include/tokenswift.h"
 #include "ts_internal.hpp"
@@ -30,6 +31,32 @@ int device_cus()
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
     if (dev >= 0 && dev < kMaxDev) cached[dev].store(cus, std::memory_order_relaxed);
     return cus;
+}
+
+// ---- the allocation-free entry point's scratch ---------------------------------------------------
+// A fixed device array stands in for the caller's workspace.  Its name is a host-side stand-in, not a
+// device address: host code uses the per-device pointer that hipGetSymbolAddress returns (each GPU
+// holds its own copy of the array at its own address), never the name.
+constexpr size_t kScratchBytes = (size_t)TS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxScratchDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxScratchDevices];   // device address of `scratch` on each device, looked up on first use
+
+int scratch_of_current_device(void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return TS_ERR_HIP;
+    if (dev < 0 || dev >= kMaxScratchDevices) return TS_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TS_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return TS_OK;
 }
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -325,6 +352,27 @@ int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
     c.n_rows = group;
     c.row_pitch = group;
     return ts::launch_combine(c, st) == hipSuccess ? TS_OK : TS_ERR_HIP;
+}
+
+int ts_partial_kv_attn_static(const ts_kv_view *kv, const void *q, int n_q_heads,
+                              const int32_t *chunk_idx, int n_sel, int chunk_size, float scale,
+                              float *out, float *lse, void *stream)
+{
+    // same validation as ts_partial_kv_attn up to the workspace (repeated here so that a shape error is not
+    // reported as a size error), then the size limit, then the same launches with the static array
+    int rc = check_view(kv, true, false);
+    if (rc != TS_OK) return rc;
+    if (!q || !chunk_idx || !out) return TS_ERR_NULL;
+    int group = 0;
+    if ((rc = check_heads(n_q_heads, kv->n_kv_heads, &group)) != TS_OK) return rc;
+    if (n_sel < 1) return TS_ERR_SHAPE;
+    if (!partial_chunk_ok(chunk_size) || !scale_ok(scale)) return TS_ERR_UNSUPPORTED;
+    PartialPlan pl;
+    plan_partial(n_q_heads, kv->n_kv_heads, n_sel, chunk_size, &pl);
+    if (pl.bytes > kScratchBytes) return TS_ERR_WORKSPACE;    // beyond the fixed scratch: use ts_partial_kv_attn
+    void *ptr = nullptr;
+    if ((rc = scratch_of_current_device(&ptr)) != TS_OK) return rc;
+    return ts_partial_kv_attn(kv, q, n_q_heads, chunk_idx, n_sel, chunk_size, scale, out, lse, ptr, kScratchBytes, stream);
 }
 
 // ts_tree_verify_attn, and with scores != nullptr ts_tree_verify_attn_scored

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_function(lib):
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(ts_[a-z_]+)\s*\(", text)))
     assert names == ["ts_append_accepted", "ts_bench_verify_split_kernel", "ts_chunk_key_sums", "ts_chunk_list_admit", "ts_chunk_scores",
-                     "ts_chunk_scores_from_sums", "ts_gather_chunks", "ts_partial_kv_attn", "ts_penalized_probs",
+                     "ts_chunk_scores_from_sums", "ts_gather_chunks", "ts_partial_kv_attn", "ts_partial_kv_attn_static", "ts_penalized_probs",
                      "ts_refresh_due", "ts_sample_tokens", "ts_sampling_workspace_bytes", "ts_stream_read_probe", "ts_strerror",
                      "ts_topk_chunks", "ts_tree_verify_attn", "ts_tree_verify_attn_scored", "ts_tune_set", "ts_version", "ts_workspace_bytes"]
     for n in names:
@@ -114,6 +114,12 @@ def test_attention_calls_reject_bad_arguments(lib, binding):
     assert pa(ws_=None) == TS_ERR_WORKSPACE and pa(wsb=16) == TS_ERR_WORKSPACE
     assert pa(ws_=ws + 16) == TS_ERR_WORKSPACE                  # not 256-byte aligned
     assert pa(out_=out + 4) == TS_ERR_ALIGN
+    # the allocation-free variant: same checks, and its fixed scratch bounds the shape (checked before any device is touched)
+    ps = lambda view=None, hq=4, n_sel=3, chunk=64, q_=q, idx_=idx, out_=out, scale=1.0: lib.ts_partial_kv_attn_static(
+        ctypes.byref(view if view is not None else _view(binding)), q_, hq, idx_, n_sel, chunk, scale, out_, None, None)
+    assert ps(idx_=None) == TS_ERR_NULL and ps(out_=None) == TS_ERR_NULL and ps(n_sel=0) == TS_ERR_SHAPE
+    assert ps(chunk=24) == TS_ERR_UNSUPPORTED and ps(scale=0.0) == TS_ERR_UNSUPPORTED
+    assert ps(hq=16, n_sel=2100) == TS_ERR_WORKSPACE               # 2 heads x 1050 partials x 8 rows x 520 B > 4 MiB
 
     def tv(parent, view=None, hq=4, ws_=ws, wsb=big, kt=0x6000, out_=out, scale=1.0):
         par = (ctypes.c_int32 * len(parent))(*parent) if parent is not None else None
