@@ -71,6 +71,10 @@ def parse():
     ap.add_argument("--hold", type=float, default=0.0,
                     help="utility mode: repeat the verification pass alone for this many seconds and exit, so that an "
                          "external tool (rocm-smi --showclocks --showpower) can sample the chip while the kernel runs")
+    ap.add_argument("--splits", type=int, default=0,
+                    help="utility: force the number of cache splits per KV head of the verification pass (0 = the library's choice); "
+                         "fewer splits than the chip has room for leave compute units idle, which shows what the pass does per "
+                         "compute unit when the chip's power limit is out of the way")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run an elementwise kernel that reads 1 GiB and writes 1 GiB (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     return ap.parse_args()
@@ -298,6 +302,8 @@ def main():
     torch.cuda.set_device(dev)
     ci = HEADLINE if args.config is None else args.config
     cfg = S.CONFIGS[ci]
+    if args.splits:
+        ts.tune_set("verify_splits", args.splits)
     w = Workload(cfg, dev, args.layers, args.tree)
     layers, n_layers, t = w.layers, w.n_layers, w.t
     hq, hkv, n = cfg.n_q_heads, cfg.n_kv_heads, cfg.n_tokens
@@ -324,8 +330,9 @@ def main():
                 w.do_verify(x)
             torch.cuda.synchronize()
             calls += len(layers)
-        print("bench.py --hold: %s, tree %d, %d verification passes in %.1f s, %.1f us each"
-              % (cfg.name, t, calls, time.time() - t_start, (time.time() - t_start) / calls * 1e6), flush=True)
+        print("bench.py --hold: %s, tree %d%s, %d verification passes in %.1f s, %.1f us each"
+              % (cfg.name, t, ", %d splits" % args.splits if args.splits else "", calls, time.time() - t_start,
+                 (time.time() - t_start) / calls * 1e6), flush=True)
         return
     run_step = step
     if args.graph:   # the calls allocate nothing and never synchronise, so a step can be captured as it is
@@ -419,8 +426,10 @@ def main():
 
     us_per_layer_step = ms_per_step * 1e3 / n_layers
     us_other = ms_other * 1e3 / n_layers
-    # beyond 128 query rows per KV head the verification pass multiplies fp16 weights with fp16 values
-    dtype = "bf16 inputs, fp32 accumulate" if cfg.group * t <= 128 else "bf16 inputs, fp32 accumulate (weights x values of the verification pass in fp16)"
+    # beyond 128 query rows per KV head (beyond 64 with 16 KV heads or more) the verification pass multiplies fp16 weights with fp16 values
+    rows = cfg.group * t
+    half = rows > 128 or (rows > 64 and hkv >= 16)
+    dtype = "bf16 inputs, fp32 accumulate" + (" (weights x values of the verification pass in fp16)" if half else "")
     res = {
         "metric": "us per layer-step: chunk scores + top-k + partial-KV attention + tree-verify attention over the full cache",
         "value": round(us_per_layer_step, 3), "unit": "us/layer-step", "n_gpus": 1, "steps": args.steps,
@@ -475,7 +484,7 @@ def main():
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, layers[0])
 
-    if args.config is None and not args.tree and not args.layers:
+    if args.config is None and not args.tree and not args.layers and not args.splits:
         # the other workloads in brief: the paper's verification width on the headline caches, then the two large
         # GQA shapes; the two small shapes eager and as a graph replay
         steps = max(4, args.steps // 2)

@@ -13,6 +13,7 @@ namespace {
 struct Tuning {
     std::atomic<int> verify_splits{0};     // 0 = heuristic
     std::atomic<int> verify_variant{0};    // 0 = default kernel shapes; 1..3 = alternatives (see verify_shape)
+    std::atomic<int> verify_kernel{0};     // 0 = by shape; k > 0 = kernel id k-1 where it can cover the rows (else by shape)
 } g_tune;
 
 // Compute units of the current device (256 on a whole MI355X, fewer on a partitioned one): the split
@@ -105,6 +106,11 @@ bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, bo
     pl->n_rows = group * n_tree;
     pl->n_rows_pad = (pl->n_rows + 15) / 16 * 16;
     if (!ts::verify_shape(pl->n_rows, n_kv_heads, g_tune.verify_variant.load(std::memory_order_relaxed), &pl->shape)) return false;
+    if (const int forced = g_tune.verify_kernel.load(std::memory_order_relaxed)) {
+        const ts::VerifyKernelInfo info = ts::verify_kernel_info(forced - 1);
+        if (info.max_rows >= pl->n_rows) pl->shape = ts::VerifyShape{forced - 1, (pl->n_rows + 31) / 32 * 32, info.wg_per_cu};
+        if (info.max_rows >= pl->n_rows && forced - 1 <= ts::kNarrow_32) pl->shape.rows_per_wg = info.max_rows;
+    }
     int n_split = 0;
     int64_t split_len = 32;
     if (n_tokens > 0) {
@@ -184,12 +190,15 @@ bool ts::verify_shape(int n_rows, int n_kv_heads, int variant, VerifyShape *out)
         else *out = VerifyShape{kWide_1x2k4, 64, 1};
     }
     else if (r <= 128) {
-        if (variant == 1) *out = VerifyShape{kWide_1x4h, 128, 2};
-        else if (variant == 2) *out = VerifyShape{kWide_1x4, 128, 2};
+        const bool many_heads = n_kv_heads >= 16;
+        // Many KV heads: each workgroup's range is long either way, and two workgroups of four wavefronts per CU
+        // measured 2-5 % faster than one of twelve; with few heads the extra partials cost more than that.  With
+        // many heads the pass draws the chip's full power (1400 W at ~1.65 GHz for 100 rows on 32 heads x 100K
+        // tokens), where the fp16 second product's smaller matrix work is worth 3 %.
+        if (variant == 1) *out = many_heads ? VerifyShape{kWide_1x4, 128, 2} : VerifyShape{kWide_1x4h, 128, 2};
+        else if (variant == 2) *out = many_heads ? VerifyShape{kWide_1x4k3, 128, 1} : VerifyShape{kWide_1x4, 128, 2};
         else if (variant == 3) *out = VerifyShape{kWide_1x4k2h, 128, 1};
-        // many KV heads: each workgroup's range is long either way, and two workgroups of four wavefronts per
-        // CU measured 2-5 % faster than one of twelve; with few heads the extra partials cost more than that
-        else if (n_kv_heads >= 16) *out = VerifyShape{kWide_1x4, 128, 2};
+        else if (many_heads) *out = VerifyShape{kWide_1x4h, 128, 2};
         else *out = VerifyShape{kWide_1x4k3, 128, 1};
     } else if (r <= 256) {
         if (variant == 1) *out = VerifyShape{kWide_1x8, 256, 1};
@@ -201,6 +210,26 @@ bool ts::verify_shape(int n_rows, int n_kv_heads, int variant, VerifyShape *out)
     }
     out->rows_per_wg = r;
     return true;
+}
+
+ts::VerifyKernelInfo ts::verify_kernel_info(int id)
+{
+    switch (id) {
+        case kNarrow_16: return {16, 5};
+        case kNarrow_32: return {32, 4};
+        case kWide_1x1: return {32, 3};
+        case kWide_1x1b: return {32, 2};
+        case kWide_1x2: case kWide_1x2h: return {64, 2};
+        case kWide_1x2k4: return {64, 1};
+        case kWide_1x4: case kWide_1x4h: return {128, 2};
+        case kWide_1x4k3: case kWide_1x4k2h: return {128, 1};
+        case kWide_2x4: case kWide_1x8: case kWide_1x8h: return {256, 1};
+        case kWide_1x10: case kWide_1x10h: return {320, 1};
+        case kWide_1x12: case kWide_1x12h: return {384, 1};
+        case kWide_2x2: return {128, 2};
+        case kWide_2x2k2: case kWide_2x2k2b: return {128, 1};
+        default: return {0, 0};
+    }
 }
 
 extern "C" {
@@ -227,6 +256,11 @@ int ts_tune_set(const char *name, int value)
     if (!name || value < 0) return TS_ERR_UNSUPPORTED;
     if (strcmp(name, "verify_splits") == 0) {
         g_tune.verify_splits = value;
+        return TS_OK;
+    }
+    if (strcmp(name, "verify_kernel") == 0) {
+        if (value > ts::kVerifyKernelCount) return TS_ERR_UNSUPPORTED;
+        g_tune.verify_kernel = value;
         return TS_OK;
     }
     if (strcmp(name, "verify_variant") == 0) {

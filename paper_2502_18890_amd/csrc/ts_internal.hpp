@@ -68,7 +68,15 @@ enum VerifyKernelId {
     kWide_1x8h,
     kWide_1x10h,
     kWide_1x12h,
+    // two row blocks per wavefront (K and V^T operands read from LDS once for both), one wavefront per SIMD
+    kWide_2x2,        // two workgroups of two wavefronts per CU
+    kWide_2x2k2,      // two key groups
+    kWide_2x2k2b,     // ... with a three-stage ring
+    kVerifyKernelCount
 };
+// rows one workgroup of a kernel covers at most, and workgroups of it a CU holds (0 rows: no such kernel)
+struct VerifyKernelInfo { int max_rows; int wg_per_cu; };
+VerifyKernelInfo verify_kernel_info(int kernel_id);
 struct VerifyShape {
     int kernel_id;
     int rows_per_wg;   // rows covered by one workgroup (multiple of 32 for the wide kernel)

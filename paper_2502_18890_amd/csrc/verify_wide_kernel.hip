@@ -290,6 +290,64 @@ verify_wide_kernel(const VerifyParams p)
     }
     if (QLDS) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the fragments are in LDS before this wavefront reaches the first barrier
 
+    // ---- fp16 pass: conversion of a landed tile's values ------------------------------------------
+    // The value half of a landed tile goes from bf16 to fp16 in place, one step before the tile is
+    // consumed; rows past the end of the range become zero (a masked key then adds 0 * 0).  The 512
+    // 16-byte pieces of a tile are shared by the WR wavefronts of its key group, kConvPieces per lane.
+    // The work is cut in three so that its arithmetic can sit between the matrix instructions of the
+    // first product (a chain of eight dependent instructions that leaves the vector unit idle):
+    // conv_load (LDS reads, issued with the key operands), conv_piece_dword (one 32-bit word: two
+    // values), conv_store.
+    constexpr int kConvPieces = (kTileKeys * 16 + WR * 64 - 1) / (WR * 64);
+    bool saw_unfit = false;
+    u32x4 conv_raw[kConvPieces], conv_out[kConvPieces];
+    uint32_t conv_big[kConvPieces];
+    auto conv_load = [&](const unsigned char *stage) {
+#pragma unroll
+        for (int i = 0; i < kConvPieces; ++i) {
+            const int pc = wave * 64 + lane + i * WR * 64;
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            conv_raw[i] = pc < kTileKeys * 16 ? *reinterpret_cast<const u32x4 *>(stage + kVHalf + pc * 16) : z;
+            conv_big[i] = 0u;
+        }
+    };
+    // word w of piece i: two values converted, their magnitudes folded into the piece's largest
+    auto conv_piece_dword = [&](int i, int w) {
+        const uint32_t x = conv_raw[i][w];
+        const f32x2 two = {bf16lo_to_f32(x), bf16hi_to_f32(x)};
+        conv_out[i][w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, f16x2));
+        // largest magnitude of the piece as a bf16 bit pattern, kept as a pair of 16-bit maxima
+        // (patterns order like the values; infinity and NaN sort above every finite value)
+        conv_big[i] = pk_max_u16(conv_big[i], x & 0x7fff7fffu);
+    };
+    auto conv_store = [&](unsigned char *stage, int64_t t0) {
+        const int64_t left = t_end - t0;
+        const int n_valid = left < 0 ? 0 : (left > kTileKeys ? kTileKeys : (int)left);
+#pragma unroll
+        for (int i = 0; i < kConvPieces; ++i) {
+            const int pc = wave * 64 + lane + i * WR * 64;
+            if (pc < kTileKeys * 16) {
+                const bool valid = (pc >> 4) < n_valid;
+                const uint32_t big = max(conv_big[i] >> 16, conv_big[i] & 0xffffu);
+                // fits: zero, or between 2^-14 (0x3880) and 65280 (0x477f, the largest bf16 below
+                // 65520, where fp16 rounds to infinity).  A piece (8 neighbouring values of one
+                // token) that is non-zero but entirely below 2^-14 would be left with a few bits only.
+                saw_unfit |= valid && big != 0u && (big - 0x3880u) >= (0x4780u - 0x3880u);
+                const u32x4 z = {0u, 0u, 0u, 0u};
+                *reinterpret_cast<u32x4 *>(stage + kVHalf + pc * 16) = valid ? conv_out[i] : z;
+            }
+        }
+    };
+    // the whole conversion at once (first tile of a pass; wavefronts without live row blocks)
+    auto convert_values = [&](unsigned char *stage, int64_t t0) {
+        conv_load(stage);
+#pragma unroll
+        for (int i = 0; i < kConvPieces; ++i)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) conv_piece_dword(i, w);
+        conv_store(stage, t0);
+    };
+
     // One 32-key tile against all of this wavefront's row blocks.  RAGGED tiles (the last one of
     // a range, every tile of the tree split) mask keys; full tiles carry no masking code.
     // L = number of row blocks computed (compile time, so that the body is straight-line code the
@@ -297,8 +355,10 @@ verify_wide_kernel(const VerifyParams p)
     // and is never written back.
 
     // ---- S^T = K . Q^T of one tile --------------------------------------------------------------
-    auto qk_tile = [&](auto live_tag, const unsigned char *stage, auto &sacc) {
+    // conv_tag: also convert the values of the tile in conv_stage (first token conv_t0), between the products
+    auto qk_tile = [&](auto live_tag, auto conv_tag, const unsigned char *stage, unsigned char *conv_stage, int64_t conv_t0, auto &sacc) {
         constexpr int L = decltype(live_tag)::value;
+        constexpr bool CONV = decltype(conv_tag)::value;
 #pragma unroll
         for (int rb = 0; rb < L; ++rb)
 #pragma unroll
@@ -308,7 +368,10 @@ verify_wide_kernel(const VerifyParams p)
         bf16x8 ka[8];
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) ka[ks] = *reinterpret_cast<const bf16x8 *>(stage + koff[ks]);
+        if constexpr (CONV) conv_load(conv_stage);
         __builtin_amdgcn_sched_barrier(0);
+        constexpr int kWords = 4 * kConvPieces;               // 32-bit words this lane converts
+        constexpr int kPerSlot = (kWords + 7) / 8;            // ... per matrix instruction of the chain
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
@@ -318,7 +381,12 @@ verify_wide_kernel(const VerifyParams p)
                                       : qf[QLDS ? 0 : rb][ks];
                 sacc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], b, sacc[rb], 0, 0, 0);
             }
+            if constexpr (CONV) {
+#pragma unroll
+                for (int c = ks * kPerSlot; c < (ks + 1) * kPerSlot && c < kWords; ++c) conv_piece_dword(c >> 2, c & 3);
+            }
         }
+        if constexpr (CONV) conv_store(conv_stage, conv_t0);
     };
 
     // Tile sums for the chunk scores (see pv_tile).  The store of a tile's sum waits until just before
@@ -473,18 +541,22 @@ verify_wide_kernel(const VerifyParams p)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 pe[e] = fast_exp2(fmaf(sacc[rb][e], p.scale_log2, (F16 ? kHalfShift : 0.f) - m_run[rb]));
-                psum += pe[e];
+                if constexpr (!F16) psum += pe[e];
             }
-            l_run[rb] += psum;
             if constexpr (F16) {
+                // the row sum is taken over the weights as the matrix instruction sees them (rounded to fp16:
+                // the normalisation then matches the product exactly), two per instruction
                 f16x8 ph[2];
+                const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
                     u32x4 w4;
 #pragma unroll
                     for (int w = 0; w < 4; ++w) {
                         const f32x2 two = {pe[8 * s + 2 * w], pe[8 * s + 2 * w + 1]};
-                        w4[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, f16x2));
+                        const f16x2 h2 = __builtin_convertvector(two, f16x2);
+                        psum = __builtin_amdgcn_fdot2(h2, ones, psum, false);
+                        w4[w] = __builtin_bit_cast(uint32_t, h2);
                     }
                     ph[s] = __builtin_bit_cast(f16x8, w4);
                 }
@@ -503,11 +575,15 @@ verify_wide_kernel(const VerifyParams p)
                         for (int w = 0; w < 4; ++w) {
                             // (halves taken as scalars: a bit_cast of one vector element to a
                             // two-element fp16 vector was seen compiled as element 0 for every w)
-                            const uint32_t had = __builtin_bit_cast(u32x4, ph[s])[w];
+                            uint32_t had = __builtin_bit_cast(u32x4, ph[s])[w];
+                            // the compiler must not compute these residuals ahead of the loop, on every tile
+                            asm volatile("" : "+v"(had));
                             const float had_lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(had & 0xffffu));
                             const float had_hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(had >> 16));
                             const f32x2 left = {pe[8 * s + 2 * w] - had_lo, pe[8 * s + 2 * w + 1] - had_hi};
-                            w4[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(left, f16x2));
+                            const f16x2 l2 = __builtin_convertvector(left, f16x2);
+                            psum = __builtin_amdgcn_fdot2(l2, ones, psum, false);
+                            w4[w] = __builtin_bit_cast(uint32_t, l2);
                         }
                         ph[s] = __builtin_bit_cast(f16x8, w4);
                     }
@@ -517,7 +593,9 @@ verify_wide_kernel(const VerifyParams p)
                         for (int cb = 0; cb < 4; ++cb)
                             oacc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, vt[cb][s]), ph[s], oacc[rb][cb], 0, 0, 0);
                 }
+                l_run[rb] += psum;
             } else {
+                l_run[rb] += psum;
                 bf16x8 p_hi[2], p_lo[2];
 #pragma unroll
                 for (int s = 0; s < 2; ++s) {
@@ -547,36 +625,6 @@ verify_wide_kernel(const VerifyParams p)
     // resident, NS-RES in flight.  Every wavefront of the workgroup runs the same number of steps
     // (one barrier each), whichever instantiation of the body it takes.
     const int n_full_steps = is_tree ? 0 : (int)(((t_end - t_begin) / kTileKeys) / KG);   // steps whose tiles are full for every key group
-    // fp16 pass: the value half of a landed tile goes from bf16 to fp16 in place; rows past the end
-    // of the range become zero (a masked key then adds 0 * 0).  A 16-byte piece per lane; the WR
-    // wavefronts of a key group share the 512 pieces of their group's tile.
-    bool saw_unfit = false;
-    auto convert_values = [&](unsigned char *stage, int64_t t0) {
-        const int64_t left = t_end - t0;
-        const int n_valid = left < 0 ? 0 : (left > kTileKeys ? kTileKeys : (int)left);
-        for (int pc = wave * 64 + lane; pc < kTileKeys * 16; pc += WR * 64) {
-            u32x4 *at = reinterpret_cast<u32x4 *>(stage + kVHalf + pc * 16);
-            const u32x4 raw = *at;
-            u32x4 cv = {0u, 0u, 0u, 0u};
-            if ((pc >> 4) < n_valid) {
-                // largest magnitude of the piece as a bf16 bit pattern (patterns order like the
-                // values; infinity and NaN sort above every finite value)
-                uint32_t big = 0u;
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const uint32_t mag = raw[w] & 0x7fff7fffu;
-                    big = max(big, max(mag >> 16, mag & 0xffffu));
-                    const f32x2 two = {bf16lo_to_f32(raw[w]), bf16hi_to_f32(raw[w])};
-                    cv[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, f16x2));
-                }
-                // fits: zero, or between 2^-14 (0x3880) and 65280 (0x477f, the largest bf16 below
-                // 65520, where fp16 rounds to infinity).  A piece (8 neighbouring values of one
-                // token) that is non-zero but entirely below 2^-14 would be left with a few bits only.
-                saw_unfit |= big != 0u && (big - 0x3880u) >= (0x4780u - 0x3880u);
-            }
-            *at = cv;
-        }
-    };
     auto pass_main = [&](auto half_tag) {
         constexpr bool F16 = decltype(half_tag)::value;
         constexpr int RES = F16 ? 2 : 1;
@@ -605,15 +653,16 @@ verify_wide_kernel(const VerifyParams p)
             // full tiles first, then the ragged end; the tree split is all ragged
             auto step = [&](auto ragged_tag) {
                 sync_and_refill();
-                if (F16) {   // the tile after this one has landed (two are resident): convert its values now
-                    uint32_t next_stage = use_stage + KG * kStageBytes;
-                    if (next_stage >= kRingBytes) next_stage = stage0;
-                    convert_values(lds + next_stage, t0_cur + KG * kTileKeys);
-                }
+                // fp16: the tile after this one has landed too (two are resident); its values are converted
+                // now, between the matrix instructions of this tile's first product
+                uint32_t next_stage = use_stage + KG * kStageBytes;
+                if (next_stage >= kRingBytes) next_stage = stage0;
                 if (L > 0) {
                     const unsigned char *stage = lds + use_stage;
-                    qk_tile(live_tag, stage, s_cur);
+                    qk_tile(live_tag, half_tag, stage, lds + next_stage, t0_cur + KG * kTileKeys, s_cur);
                     pv_tile(live_tag, ragged_tag, half_tag, stage, t0_cur, s_cur);
+                } else if (F16) {
+                    convert_values(lds + next_stage, t0_cur + KG * kTileKeys);
                 }
                 use_stage += KG * kStageBytes;
                 if (use_stage >= kRingBytes) use_stage = stage0;
@@ -762,6 +811,9 @@ hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t 
         case kWide_1x10h: return launch_one<1, 10, 1, 4, 3, true, true>(p, stream);
         case kWide_1x12h: return launch_one<1, 12, 1, 3, 3, true, true>(p, stream);
         case kWide_1x12: return launch_one<1, 12, 1, 3, 3, true>(p, stream);
+        case kWide_2x2: return launch_one<2, 2, 1, 4, 1, false>(p, stream);
+        case kWide_2x2k2: return launch_one<2, 2, 2, 4, 1, false>(p, stream);
+        case kWide_2x2k2b: return launch_one<2, 2, 2, 3, 1, false>(p, stream);
         default: return hipErrorInvalidValue;
     }
 }
