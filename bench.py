@@ -71,6 +71,8 @@ def parse():
     ap.add_argument("--hold", type=float, default=0.0,
                     help="utility mode: repeat the verification pass alone for this many seconds and exit, so that an "
                          "external tool (rocm-smi --showclocks --showpower) can sample the chip while the kernel runs")
+    ap.add_argument("--hold-what", choices=("verify", "stream-read"), default="verify",
+                    help="what --hold repeats: the verification pass, or the kernel of nothing but loads over the same K and V buffers")
     ap.add_argument("--splits", type=int, default=0,
                     help="utility: force the number of cache splits per KV head of the verification pass (0 = the library's choice); "
                          "fewer splits than the chip has room for leave compute units idle, which shows what the pass does per "
@@ -325,14 +327,24 @@ def main():
     assert same_sets > 0.98, "scores from the verification pass select other chunks than the scoring pass (%.3f)" % same_sets
     if args.hold > 0:
         t_start, calls = time.time(), 0
+        sink0 = torch.zeros(1, dtype=torch.int32, device=dev)
         while time.time() - t_start < args.hold:
             for x in layers:
-                w.do_verify(x)
+                if args.hold_what == "verify":
+                    w.do_verify(x)
+                else:
+                    ts.stream_read_probe(x["k"], sink0)
+                    ts.stream_read_probe(x["v"], sink0)
             torch.cuda.synchronize()
             calls += len(layers)
-        print("bench.py --hold: %s, tree %d%s, %d verification passes in %.1f s, %.1f us each"
-              % (cfg.name, t, ", %d splits" % args.splits if args.splits else "", calls, time.time() - t_start,
-                 (time.time() - t_start) / calls * 1e6), flush=True)
+        dt = time.time() - t_start
+        if args.hold_what == "verify":
+            print("bench.py --hold: %s, tree %d%s, %d verification passes in %.1f s, %.1f us each"
+                  % (cfg.name, t, ", %d splits" % args.splits if args.splits else "", calls, dt, dt / calls * 1e6), flush=True)
+        else:
+            nbytes = 2 * layers[0]["k"].numel() * 2
+            print("bench.py --hold: %s, %d plain reads of one layer's K and V (%d bytes) in %.1f s, %.1f us each, %.0f GB/s"
+                  % (cfg.name, calls, nbytes, dt, dt / calls * 1e6, nbytes * calls / dt / 1e9), flush=True)
         return
     run_step = step
     if args.graph:   # the calls allocate nothing and never synchronise, so a step can be captured as it is
