@@ -73,6 +73,9 @@ def parse():
                          "external tool (rocm-smi --showclocks --showpower) can sample the chip while the kernel runs")
     ap.add_argument("--hold-what", choices=("verify", "stream-read"), default="verify",
                     help="what --hold repeats: the verification pass, or the kernel of nothing but loads over the same K and V buffers")
+    ap.add_argument("--zero-cache", action="store_true",
+                    help="utility: fill every layer's K and V with zeros before timing (same instructions, same bytes moved, "
+                         "fewer bits toggling in the multipliers: shows how much of a pass's time is set by power)")
     ap.add_argument("--splits", type=int, default=0,
                     help="utility: force the number of cache splits per KV head of the verification pass (0 = the library's choice); "
                          "fewer splits than the chip has room for leave compute units idle, which shows what the pass does per "
@@ -308,6 +311,10 @@ def main():
         ts.tune_set("verify_splits", args.splits)
     w = Workload(cfg, dev, args.layers, args.tree)
     layers, n_layers, t = w.layers, w.n_layers, w.t
+    if args.zero_cache:
+        for x in layers:
+            x["k"].zero_()
+            x["v"].zero_()
     hq, hkv, n = cfg.n_q_heads, cfg.n_kv_heads, cfg.n_tokens
     scores, idx = w.scores, w.idx
 
@@ -324,7 +331,7 @@ def main():
     idx_a = idx.clone()
     w.do_verify_scored(x0); w.do_topk(x0)
     same_sets = sum(len(set(a.tolist()) & set(b.tolist())) for a, b in zip(idx_a.cpu(), idx.cpu())) / float(idx.numel())
-    assert same_sets > 0.98, "scores from the verification pass select other chunks than the scoring pass (%.3f)" % same_sets
+    assert same_sets > 0.98 or args.zero_cache, "scores from the verification pass select other chunks than the scoring pass (%.3f)" % same_sets
     if args.hold > 0:
         t_start, calls = time.time(), 0
         sink0 = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -339,8 +346,9 @@ def main():
             calls += len(layers)
         dt = time.time() - t_start
         if args.hold_what == "verify":
-            print("bench.py --hold: %s, tree %d%s, %d verification passes in %.1f s, %.1f us each"
-                  % (cfg.name, t, ", %d splits" % args.splits if args.splits else "", calls, dt, dt / calls * 1e6), flush=True)
+            print("bench.py --hold: %s, tree %d%s%s, %d verification passes in %.1f s, %.1f us each"
+                  % (cfg.name, t, ", %d splits" % args.splits if args.splits else "", ", cache of zeros" if args.zero_cache else "",
+                     calls, dt, dt / calls * 1e6), flush=True)
         else:
             nbytes = 2 * layers[0]["k"].numel() * 2
             print("bench.py --hold: %s, %d plain reads of one layer's K and V (%d bytes) in %.1f s, %.1f us each, %.0f GB/s"
@@ -496,7 +504,7 @@ def main():
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, layers[0])
 
-    if args.config is None and not args.tree and not args.layers and not args.splits:
+    if args.config is None and not args.tree and not args.layers and not args.splits and not args.zero_cache:
         # the other workloads in brief: the paper's verification width on the headline caches, then the two large
         # GQA shapes; the two small shapes eager and as a graph replay
         steps = max(4, args.steps // 2)

@@ -330,7 +330,9 @@ int ts_sample_tokens(const float *probs, int n_rows, int64_t vocab, int method, 
 /*
  * Tuning hook (not needed for correct results): overrides a launch-geometry choice until
  * reset with value 0.  Names: "verify_splits" (number of cache splits per KV head);
- * "verify_variant" (1..3: alternative kernel shapes of the verification pass).  Every setting
+ * "verify_variant" (1..3: alternative kernel shapes of the verification pass); "verify_kernel" (k > 0: the
+ * k-th instantiation of the verification kernels wherever it can cover the call's query rows per KV head, the
+ * default shape elsewhere: lets tests and measurements reach every instantiation).  Every setting
  * produces the same results up to rounding order.  Returns TS_OK, or TS_ERR_UNSUPPORTED for an
  * unknown name or a value the kernels cannot run.  The same setting is seen by ts_workspace_bytes,
  * so size the workspace after setting it.  This is the only mutable state of the library (process-wide,

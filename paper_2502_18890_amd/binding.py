@@ -141,6 +141,21 @@ def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> torch.
     return workspace
 
 
+_parent_cache: dict = {}
+
+
+def _parent_array(parent: Sequence[int]):
+    """Host int32 array of the tree for the C call; the same tree is usually passed call after call."""
+    key = (len(parent), str(parent.dtype), parent.tobytes()) if hasattr(parent, "tobytes") else tuple(int(x) for x in parent)
+    arr = _parent_cache.get(key)
+    if arr is None:
+        if len(_parent_cache) > 256:
+            _parent_cache.clear()
+        arr = (ctypes.c_int32 * len(parent))(*[int(x) for x in parent])
+        _parent_cache[key] = arr
+    return arr
+
+
 def chunk_scores(q: torch.Tensor, k: torch.Tensor, chunk_size: int, scale: float,
                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """q [Hq,128] bf16, k [Hkv,N,128] bf16 view -> scores fp32 [Hkv, ceil(N/chunk_size)]."""
@@ -178,8 +193,9 @@ def partial_kv_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, chunk_idx
     q = q.contiguous()
     chunk_idx = chunk_idx.contiguous()
     hq = q.shape[0]
-    nbytes = workspace_bytes(OP_PARTIAL_ATTN, hq, k.shape[0], k.shape[1], 0, chunk_idx.shape[1], chunk_size)
-    workspace = _workspace(nbytes, k.device, workspace)
+    if workspace is None:   # a caller's workspace is checked by the library itself
+        workspace = _workspace(workspace_bytes(OP_PARTIAL_ATTN, hq, k.shape[0], k.shape[1], 0, chunk_idx.shape[1], chunk_size),
+                               k.device, None)
     if out is None:
         out = torch.empty(hq, HEAD_DIM, dtype=torch.float32, device=k.device)
     if lse is None and want_lse:
@@ -224,12 +240,13 @@ def tree_verify_attn(q_tree: torch.Tensor, k: Optional[torch.Tensor], v: Optiona
     hkv = k_tree.shape[1]
     kv = _view(k, v, hkv)
     n_tokens = 0 if k is None else k.shape[1]
-    par = (ctypes.c_int32 * len(parent))(*[int(x) for x in parent])
     if len(parent) != t:
         raise ValueError("parent must have one entry per tree node")
+    par = _parent_array(parent)
     scored = score_chunk > 0
-    nbytes = workspace_bytes(OP_TREE_VERIFY_SCORED if scored else OP_TREE_VERIFY, hq, hkv, n_tokens, t)
-    workspace = _workspace(nbytes, q_tree.device, workspace)
+    if workspace is None:   # a caller's workspace is checked by the library itself
+        workspace = _workspace(workspace_bytes(OP_TREE_VERIFY_SCORED if scored else OP_TREE_VERIFY, hq, hkv, n_tokens, t),
+                               q_tree.device, None)
     if out is None:
         out = torch.empty(t, hq, HEAD_DIM, dtype=torch.float32, device=q_tree.device)
     if lse is None and want_lse:

@@ -155,6 +155,19 @@ def test_attention_calls_reject_bad_arguments(lib, binding):
     assert tvs([-1, 0], wsb=need_plain) == TS_ERR_WORKSPACE
 
 
+def test_bench_split_kernel_entry_rejects_bad_arguments(lib, binding):
+    ws, big = 0x10000, 1 << 30
+    def sk(parent, view=None, hq=4, sums=0, ws_=ws, wsb=big, q_=0x3000):
+        par = (ctypes.c_int32 * len(parent))(*parent)
+        return lib.ts_bench_verify_split_kernel(ctypes.byref(view if view is not None else _view(binding)), q_, hq, 0x6000, 0x7000,
+                                                par, len(parent), 1.0, sums, ws_, wsb, None)
+    assert sk([-1, 0], q_=None) == TS_ERR_NULL and sk([0, 0]) == TS_ERR_TREE and sk([-1, 0], hq=3) == TS_ERR_SHAPE
+    assert sk([-1, 0], ws_=None) == TS_ERR_WORKSPACE and sk([-1, 0], wsb=64) == TS_ERR_WORKSPACE
+    assert sk([-1, 0], sums=1, view=_view(binding, n=0, k=None, v=None)) == TS_ERR_SHAPE
+    need_plain = binding.workspace_bytes(binding.OP_TREE_VERIFY, 4, 2, 100, 2)
+    assert sk([-1, 0], sums=1, wsb=need_plain) == TS_ERR_WORKSPACE        # the variant with tile sums needs the larger workspace
+
+
 def test_tune_set(lib):
     assert lib.ts_tune_set(b"verify_splits", 7) == TS_OK
     assert lib.ts_tune_set(b"verify_splits", 0) == TS_OK
@@ -163,6 +176,7 @@ def test_tune_set(lib):
     assert lib.ts_tune_set(None, 1) == TS_ERR_UNSUPPORTED
     assert lib.ts_tune_set(b"verify_stage", 1) == TS_ERR_UNSUPPORTED      # no knob may leave a product call without its output
     assert lib.ts_tune_set(b"verify_variant", 4) == TS_ERR_UNSUPPORTED and lib.ts_tune_set(b"verify_variant", 0) == TS_OK
+    assert lib.ts_tune_set(b"verify_kernel", 1000) == TS_ERR_UNSUPPORTED and lib.ts_tune_set(b"verify_kernel", 0) == TS_OK
 
 
 def test_stream_read_probe_rejects_bad_arguments(lib):

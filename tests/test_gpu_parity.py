@@ -342,6 +342,30 @@ def test_verify_kernel_variants(ts, variant, hq, hkv, n, t):
     assert_close(lse, rlse, "verify lse variant=%d" % variant)
 
 
+# every instantiation of the two verification kernels, by its position in the library's list of kernel shapes, with the
+# largest number of query rows per KV head it covers (the "verify_kernel" override falls back to the default shape when
+# a kernel cannot cover the rows, so each case below really runs the kernel it names)
+KERNEL_ROWS = [16, 32, 32, 32, 64, 64, 128, 128, 256, 256, 320, 384, 64, 128, 128, 256, 320, 384, 128, 128, 128]
+ROW_SHAPES = {16: [(4, 4, 16), (2, 2, 5)], 32: [(8, 4, 16), (4, 4, 23)], 64: [(8, 2, 16), (12, 4, 17)], 128: [(32, 8, 32), (4, 4, 100), (8, 2, 27)],
+              256: [(32, 8, 64), (8, 2, 51)], 320: [(40, 8, 64), (10, 2, 57)], 384: [(48, 8, 64), (6, 1, 61)]}
+
+
+@pytest.mark.parametrize("kernel_id", range(len(KERNEL_ROWS)))
+def test_verify_every_kernel_instantiation(ts, kernel_id):
+    """All shapes of the verification kernels, including those no default geometry selects, on a full row count and on a
+    ragged one; the cache length leaves a ragged last tile and, for the kernels with key groups, tiles past the end."""
+    for hq, hkv, t in ROW_SHAPES[KERNEL_ROWS[kernel_id]]:
+        c = _case(40 + kernel_id, hq, hkv, 1229, t)
+        parent = _random_parent(c["rng"], t)
+        try:
+            ts.tune_set("verify_kernel", kernel_id + 1)
+            out, lse, ref, rlse = _verify_both(ts, c, parent)
+        finally:
+            ts.tune_set("verify_kernel", 0)
+        assert_close(out, ref, "verify out kernel %d rows %d" % (kernel_id, hq // hkv * t))
+        assert_close(lse, rlse, "verify lse kernel %d rows %d" % (kernel_id, hq // hkv * t))
+
+
 @pytest.mark.parametrize("hq,hkv,n,t", [(32, 8, 2085, 64), (40, 8, 700, 64), (16, 4, 900, 32), (48, 8, 333, 64), (8, 2, 500, 32)])
 @pytest.mark.parametrize("kind", ["huge", "tiny"])
 @pytest.mark.parametrize("variant", [0, 1, 3])
