@@ -61,6 +61,7 @@ constexpr int kVHalf = kTileKeys * 256;
 constexpr int kQRowBytes = 272;                // padded query rows (QLDS)
 constexpr float kRescaleSlack = 8.0f;          // log2 units
 constexpr float kResidualShare = 1.0f / 8.0f;    // share of a row's running denominator from which a weight counts as concentrated
+constexpr float kTinyShare = 1.0f / 1024.0f;    // a row whose largest output is below this share of its weight sum counts as too small for fp16 values
 constexpr float kHalfShift = 6.0f;             // fp16 weights are taken 2^6 above the reference: at most 2^14, flushed below 2^-30 of that
 
 template <int N>
@@ -95,12 +96,13 @@ constexpr int loads_per_wave(int wr) { return wr >= 16 ? 1 : (wr >= 8 ? 2 : (wr 
 // work in a kernel whose clock is limited by power.  V is bf16 in HBM, so the value half of a tile
 // is converted to fp16 in LDS, in place, one step before the tile is consumed (each wavefront
 // converts a slice; two tiles are resident instead of one).  bf16 -> fp16 is exact for magnitudes
-// in [2^-14, 65504].  Smaller ones keep an absolute error below 2^-25, harmless next to a
-// neighbour of normal size; larger ones, NaN, and tokens whose 8-value pieces are non-zero but
-// wholly below 2^-14 do not fit.  A workgroup that meets such a value finishes its fp16 pass,
-// finds the note its wavefronts left in LDS, and runs its range again with bf16 weights and
-// residuals: the result never depends on fp16's range, and workgroups that meet no such value
-// pay one barrier for the check.
+// in [2^-17, 65504] (down to 2^-14 as normal numbers, below that as subnormals whose spacing of 2^-24 still
+// holds a bf16 value's eight bits).  Smaller ones keep an absolute error below 2^-25, harmless next to
+// values of normal size; larger ones and NaN become infinity or NaN.  Whether that happened is read off the
+// accumulators at the end of the pass (non-finite entries; rows whose whole output is tiny although
+// non-zero values were converted): such a workgroup runs its range again with bf16 weights and
+// residuals, so the result never depends on fp16's range, and workgroups that meet no such value pay
+// two barriers and a scan of their accumulators for the check.
 template <int NRB, int WR, int KG, int NS, int OCC, bool QLDS, bool HALF>
 __global__ void __launch_bounds__(64 * WR * KG) __attribute__((amdgpu_waves_per_eu(OCC, OCC)))
 verify_wide_kernel(const VerifyParams p)
@@ -139,6 +141,9 @@ verify_wide_kernel(const VerifyParams p)
         t_begin = (int64_t)split * p.split_len;
         t_end = t_begin + p.split_len < p.n_tokens ? t_begin + p.split_len : p.n_tokens;
     }
+    // Positions inside the range are 32-bit offsets from its first token (a range is shorter than 2^31 tokens: the
+    // host refuses longer caches), so that the per-step tests are scalar 32-bit compares.
+    const int range_len = (int)(t_end - t_begin);
 
     // ---- rows of this wavefront: 32-row blocks wave, wave + WR, ... of the workgroup's row tile ----
     const int tile_row0 = blockIdx.z * p.rows_per_wg;
@@ -193,13 +198,16 @@ verify_wide_kernel(const VerifyParams p)
     const uint32_t stage0 = kg * kStageBytes;
     const int64_t tile_elems = (int64_t)KG * kTileKeys * tstride;      // elements between consecutive group tiles
     const uint16_t *kfill, *vfill;
-    int64_t fill_rem;          // bytes from the first row of the next tile to fill up to the end of the last valid row (<= 0: none)
+    int fill_rel;              // offset in the range of the first row of the next tile to fill
     uint32_t fill_stage;
     uint32_t use_stage;        // stage of the group tile being consumed
-    int64_t t0_cur;            // its first token
+    int rel_cur;               // offset in the range of its first token
+    const uint32_t row_bytes = (uint32_t)(tstride * 2);   // <= 2^25
     auto issue_tile = [&]() {
         if (loader) {
-            const uint32_t nrec = fill_rem <= 0 ? 0u : (fill_rem > 0xffffffffLL ? 0xffffffffu : (uint32_t)fill_rem);
+            // bytes from the tile's first row up to the end of its last valid row (0: the tile lies past the range)
+            const int rows = range_len - fill_rel;
+            const uint32_t nrec = rows <= 0 ? 0u : (uint32_t)((rows < kTileKeys ? rows : kTileKeys) - 1) * row_bytes + 256u;
             const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(kfill), 0, nrec, 0x00020000);
             const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(vfill), 0, nrec, 0x00020000);
             unsigned char *stage = lds + fill_stage;
@@ -214,7 +222,7 @@ verify_wide_kernel(const VerifyParams p)
             }
             kfill += tile_elems;     // past the range the descriptor covers 0 bytes, so the base is never dereferenced
             vfill += tile_elems;
-            fill_rem -= tile_elems * 2;
+            fill_rel += KG * kTileKeys;
             fill_stage += KG * kStageBytes;
             if (fill_stage >= kRingBytes) fill_stage = stage0;
         }
@@ -234,8 +242,8 @@ verify_wide_kernel(const VerifyParams p)
             voff[cb] = kVHalf + (4 * hh + i4) * 256 + ((4 * (cb ^ i4) + 2 * mh + (ilo >> 1)) << 4) + ((ilo & 1) << 3);
     }
 
-    const int64_t n_tiles = (t_end - t_begin + kTileKeys - 1) / kTileKeys;
-    const int n_steps = (int)((n_tiles + KG - 1) / KG);   // group tiles per key group (some groups may run one empty)
+    const int n_tiles = (range_len + kTileKeys - 1) / kTileKeys;
+    const int n_steps = (n_tiles + KG - 1) / KG;   // group tiles per key group (some groups may run one empty)
     // ---- start of a pass over the range (a workgroup makes one, or two if fp16 did not fit) ----
     constexpr int kLdsUsed = KG * NS * kStageBytes + (QLDS ? 32 * NRB * WR * kQRowBytes : 0);
     uint32_t *unfit_note = reinterpret_cast<uint32_t *>(lds + kLdsUsed);   // 16 bytes behind everything else
@@ -246,7 +254,7 @@ verify_wide_kernel(const VerifyParams p)
         {
             const u32x4 z = {0u, 0u, 0u, 0u};
             for (int off = tid * 16; off < KG * NS * kStageBytes; off += NT * 16) *reinterpret_cast<u32x4 *>(lds + off) = z;
-            if (first && tid == 0) *unfit_note = 0u;
+            if (first && tid == 0) *reinterpret_cast<u32x2 *>(unfit_note) = u32x2{0u, 0u};
         }
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS traffic only
 #pragma unroll
@@ -261,10 +269,10 @@ verify_wide_kernel(const VerifyParams p)
         }
         kfill = kbase + (t_begin + (int64_t)kg * kTileKeys) * tstride;
         vfill = vbase + (t_begin + (int64_t)kg * kTileKeys) * tstride;
-        fill_rem = (t_end - (t_begin + (int64_t)kg * kTileKeys) - 1) * tstride * 2 + 256;
+        fill_rel = kg * kTileKeys;
         fill_stage = stage0;
         use_stage = stage0;
-        t0_cur = t_begin + (int64_t)kg * kTileKeys;
+        rel_cur = kg * kTileKeys;
 #pragma unroll
         for (int s = 0; s < NS - RES; ++s) issue_tile();   // tiles past the range load nothing but still count
     };
@@ -299,53 +307,51 @@ verify_wide_kernel(const VerifyParams p)
     // conv_load (LDS reads, issued with the key operands), conv_piece_dword (one 32-bit word: two
     // values), conv_store.
     constexpr int kConvPieces = (kTileKeys * 16 + WR * 64 - 1) / (WR * 64);
-    bool saw_unfit = false;
     u32x4 conv_raw[kConvPieces], conv_out[kConvPieces];
-    uint32_t conv_big[kConvPieces];
+    uint32_t conv_seen = 0u;   // every bit that was set in any value this lane converted (zero: it saw nothing but zeros)
     auto conv_load = [&](const unsigned char *stage) {
 #pragma unroll
         for (int i = 0; i < kConvPieces; ++i) {
             const int pc = wave * 64 + lane + i * WR * 64;
             const u32x4 z = {0u, 0u, 0u, 0u};
             conv_raw[i] = pc < kTileKeys * 16 ? *reinterpret_cast<const u32x4 *>(stage + kVHalf + pc * 16) : z;
-            conv_big[i] = 0u;
         }
     };
-    // word w of piece i: two values converted, their magnitudes folded into the piece's largest
+    // word w of piece i: two values converted
     auto conv_piece_dword = [&](int i, int w) {
         const uint32_t x = conv_raw[i][w];
         const f32x2 two = {bf16lo_to_f32(x), bf16hi_to_f32(x)};
         conv_out[i][w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, f16x2));
-        // largest magnitude of the piece as a bf16 bit pattern, kept as a pair of 16-bit maxima
-        // (patterns order like the values; infinity and NaN sort above every finite value)
-        conv_big[i] = pk_max_u16(conv_big[i], x & 0x7fff7fffu);
     };
-    auto conv_store = [&](unsigned char *stage, int64_t t0) {
-        const int64_t left = t_end - t0;
-        const int n_valid = left < 0 ? 0 : (left > kTileKeys ? kTileKeys : (int)left);
+    // rel: offset in the range of the tile's first token
+    auto conv_store = [&](unsigned char *stage, int rel) {
+        const int left = range_len - rel;
+        const int n_valid = left < 0 ? 0 : (left > kTileKeys ? kTileKeys : left);   // wavefront-uniform
 #pragma unroll
         for (int i = 0; i < kConvPieces; ++i) {
             const int pc = wave * 64 + lane + i * WR * 64;
             if (pc < kTileKeys * 16) {
-                const bool valid = (pc >> 4) < n_valid;
-                const uint32_t big = max(conv_big[i] >> 16, conv_big[i] & 0xffffu);
-                // fits: zero, or between 2^-14 (0x3880) and 65280 (0x477f, the largest bf16 below
-                // 65520, where fp16 rounds to infinity).  A piece (8 neighbouring values of one
-                // token) that is non-zero but entirely below 2^-14 would be left with a few bits only.
-                saw_unfit |= valid && big != 0u && (big - 0x3880u) >= (0x4780u - 0x3880u);
-                const u32x4 z = {0u, 0u, 0u, 0u};
-                *reinterpret_cast<u32x4 *>(stage + kVHalf + pc * 16) = valid ? conv_out[i] : z;
+                u32x4 *at = reinterpret_cast<u32x4 *>(stage + kVHalf + pc * 16);
+                if (n_valid == kTileKeys) {       // the usual case: no row to blank
+                    conv_seen |= conv_raw[i][0] | conv_raw[i][1] | conv_raw[i][2] | conv_raw[i][3];
+                    *at = conv_out[i];
+                } else {
+                    const bool valid = (pc >> 4) < n_valid;
+                    if (valid) conv_seen |= conv_raw[i][0] | conv_raw[i][1] | conv_raw[i][2] | conv_raw[i][3];
+                    const u32x4 z = {0u, 0u, 0u, 0u};
+                    *at = valid ? conv_out[i] : z;
+                }
             }
         }
     };
     // the whole conversion at once (first tile of a pass; wavefronts without live row blocks)
-    auto convert_values = [&](unsigned char *stage, int64_t t0) {
+    auto convert_values = [&](unsigned char *stage, int rel) {
         conv_load(stage);
 #pragma unroll
         for (int i = 0; i < kConvPieces; ++i)
 #pragma unroll
             for (int w = 0; w < 4; ++w) conv_piece_dword(i, w);
-        conv_store(stage, t0);
+        conv_store(stage, rel);
     };
 
     // One 32-key tile against all of this wavefront's row blocks.  RAGGED tiles (the last one of
@@ -356,7 +362,7 @@ verify_wide_kernel(const VerifyParams p)
 
     // ---- S^T = K . Q^T of one tile --------------------------------------------------------------
     // conv_tag: also convert the values of the tile in conv_stage (first token conv_t0), between the products
-    auto qk_tile = [&](auto live_tag, auto conv_tag, const unsigned char *stage, unsigned char *conv_stage, int64_t conv_t0, auto &sacc) {
+    auto qk_tile = [&](auto live_tag, auto conv_tag, const unsigned char *stage, unsigned char *conv_stage, int conv_rel, auto &sacc) {
         constexpr int L = decltype(live_tag)::value;
         constexpr bool CONV = decltype(conv_tag)::value;
 #pragma unroll
@@ -386,7 +392,7 @@ verify_wide_kernel(const VerifyParams p)
                 for (int c = ks * kPerSlot; c < (ks + 1) * kPerSlot && c < kWords; ++c) conv_piece_dword(c >> 2, c & 3);
             }
         }
-        if constexpr (CONV) conv_store(conv_stage, conv_t0);
+        if constexpr (CONV) conv_store(conv_stage, conv_rel);
     };
 
     // Tile sums for the chunk scores (see pv_tile).  The store of a tile's sum waits until just before
@@ -394,10 +400,11 @@ verify_wide_kernel(const VerifyParams p)
     // the loads a step waits for would put its own latency on that wait.
     const bool scoring = p.tile_sums != nullptr && wave == 0 && blockIdx.z == 0 && !is_tree;   // wavefront-uniform
     float score_parked = 0.f;
-    int64_t score_parked_tile = -1;
+    int score_parked_tile = -1;   // tile of the range (cache ranges begin on a tile boundary)
+    float *const tile_sums_range = scoring ? p.tile_sums + (int64_t)h * p.tile_sums_stride + (t_begin >> 5) : nullptr;
     auto score_flush = [&]() {
         if (scoring && score_parked_tile >= 0) {
-            if (lane == 0) p.tile_sums[(int64_t)h * p.tile_sums_stride + score_parked_tile] = score_parked;
+            if (lane == 0) tile_sums_range[score_parked_tile] = score_parked;
             score_parked_tile = -1;
         }
     };
@@ -405,7 +412,7 @@ verify_wide_kernel(const VerifyParams p)
     // ---- softmax of one tile's logits and O^T += V^T . P^T ----------------------------------------
     // RAGGED tiles (the last one of a range, every tile of the tree split) mask keys; full tiles
     // carry no masking code.
-    auto pv_tile = [&](auto live_tag, auto ragged_tag, auto half_tag, const unsigned char *stage, int64_t t0, auto &sacc) {
+    auto pv_tile = [&](auto live_tag, auto ragged_tag, auto half_tag, const unsigned char *stage, int rel, auto &sacc) {
         constexpr int L = decltype(live_tag)::value;
         constexpr bool RAGGED = decltype(ragged_tag)::value;
         constexpr bool F16 = decltype(half_tag)::value;
@@ -458,9 +465,9 @@ verify_wide_kernel(const VerifyParams p)
         // in wavefront 0 of every key group) hold exactly the raw logits q.k that Eq. 2 sums; their sum
         // over the tile's valid keys is parked until the next tile's loads are about to be issued (see
         // score_flush), and the merge kernel turns tiles into chunks.
-        if (L > 0 && scoring && t0 < t_end) {
+        if (L > 0 && scoring && rel < range_len) {
             float ssum = 0.f;
-            const uint32_t ok = RAGGED ? (uint32_t)((t_end - t0 >= 32 ? 0xffffffffull : ((1ull << (t_end - t0)) - 1ull)) >> (hh * 4)) : 0xffffffffu;
+            const uint32_t ok = RAGGED ? (uint32_t)((range_len - rel >= 32 ? 0xffffffffull : ((1ull << (range_len - rel)) - 1ull)) >> (hh * 4)) : 0xffffffffu;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const float v = sacc[0][e];
@@ -468,7 +475,7 @@ verify_wide_kernel(const VerifyParams p)
             }
             ssum = swap32_sum(ssum);                                     // the two lanes that share row n32
             score_parked = row16_sum(n32 < p.group ? ssum : 0.f);       // the group's heads (group <= 8: one 16-lane row)
-            score_parked_tile = t0 >> 5;
+            score_parked_tile = rel >> 5;
         }
 
         // m_run is a reference point, not necessarily the exact running maximum: the accumulators are
@@ -484,13 +491,13 @@ verify_wide_kernel(const VerifyParams p)
         for (int rb = 0; rb < L; ++rb) {
             if (RAGGED) {
                 uint64_t tile_ok;
-                if (t0 >= t_end) {   // a key group's tile past the end of the range: no keys
+                if (rel >= range_len) {   // a key group's tile past the end of the range: no keys
                     tile_ok = 0ull;
-                } else if (is_tree) {
-                    const uint64_t w = (t0 & 64) ? amask_hi[rb] : amask_lo[rb];
-                    tile_ok = w >> (t0 & 63);
+                } else if (is_tree) {     // the tree's range begins at node 0
+                    const uint64_t w = (rel & 64) ? amask_hi[rb] : amask_lo[rb];
+                    tile_ok = w >> (rel & 63);
                 } else {
-                    tile_ok = t_end - t0 >= 64 ? ~0ull : ((1ull << (t_end - t0)) - 1ull);
+                    tile_ok = range_len - rel >= 64 ? ~0ull : ((1ull << (range_len - rel)) - 1ull);
                 }
                 const uint32_t vm = (uint32_t)tile_ok >> (hh * 4);
 #pragma unroll
@@ -624,7 +631,7 @@ verify_wide_kernel(const VerifyParams p)
     // Main loop over group tiles u = 0 .. n_steps-1 (tile u*KG + kg of the range): RES group tiles
     // resident, NS-RES in flight.  Every wavefront of the workgroup runs the same number of steps
     // (one barrier each), whichever instantiation of the body it takes.
-    const int n_full_steps = is_tree ? 0 : (int)(((t_end - t_begin) / kTileKeys) / KG);   // steps whose tiles are full for every key group
+    const int n_full_steps = is_tree ? 0 : (range_len / kTileKeys) / KG;   // steps whose tiles are full for every key group
     auto pass_main = [&](auto half_tag) {
         constexpr bool F16 = decltype(half_tag)::value;
         constexpr int RES = F16 ? 2 : 1;
@@ -648,7 +655,7 @@ verify_wide_kernel(const VerifyParams p)
             f32x16 s_cur[L > 0 ? L : 1];
             if (F16) {   // the first tile's values are converted before the loop; the barrier of step 0 publishes them
                 sync_and_refill();
-                convert_values(lds + use_stage, t0_cur);
+                convert_values(lds + use_stage, rel_cur);
             }
             // full tiles first, then the ragged end; the tree split is all ragged
             auto step = [&](auto ragged_tag) {
@@ -659,14 +666,14 @@ verify_wide_kernel(const VerifyParams p)
                 if (next_stage >= kRingBytes) next_stage = stage0;
                 if (L > 0) {
                     const unsigned char *stage = lds + use_stage;
-                    qk_tile(live_tag, half_tag, stage, lds + next_stage, t0_cur + KG * kTileKeys, s_cur);
-                    pv_tile(live_tag, ragged_tag, half_tag, stage, t0_cur, s_cur);
+                    qk_tile(live_tag, half_tag, stage, lds + next_stage, rel_cur + KG * kTileKeys, s_cur);
+                    pv_tile(live_tag, ragged_tag, half_tag, stage, rel_cur, s_cur);
                 } else if (F16) {
-                    convert_values(lds + next_stage, t0_cur + KG * kTileKeys);
+                    convert_values(lds + next_stage, rel_cur + KG * kTileKeys);
                 }
                 use_stage += KG * kStageBytes;
                 if (use_stage >= kRingBytes) use_stage = stage0;
-                t0_cur += KG * kTileKeys;
+                rel_cur += KG * kTileKeys;
             };
             for (int u = 0; u < n_full_steps; ++u) step(std::false_type{});
             for (int u = n_full_steps; u < n_steps; ++u) step(std::true_type{});
@@ -679,10 +686,35 @@ verify_wide_kernel(const VerifyParams p)
     float m_shift = 0.f;   // how far above the reference point the weights of the pass that counts were taken
     if constexpr (HALF) {
         pass_main(std::true_type{});
-        // did any wavefront of this workgroup meet a value that fp16 cannot hold?
-        if (__builtin_amdgcn_ballot_w64(saw_unfit) != 0ull && lane == 0) *unfit_note = 1u;
+        // Did fp16 hold the values of this range?  Judged from the result, once per pass: a value of 65520 or
+        // more (or a NaN) became an infinity (NaN) in LDS and has made every accumulator of its column
+        // non-finite, whatever its weight (0 * inf is NaN too); values below 2^-17 lost bits (2^-25 absolute at
+        // most), which matters only where a row's whole output is that small: a row whose largest output
+        // magnitude is below kTinyShare of its weight sum, although non-zero values were converted.
+        if (__builtin_amdgcn_ballot_w64((conv_seen & 0x7fff7fffu) != 0u) != 0ull && lane == 0) unfit_note[1] = 1u;
+        bool bad = false, tiny = false;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+            if (rb < nrb_live) {
+                float sum = 0.f, big = 0.f;
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const float a = fabsf(oacc[rb][cb][e]);
+                        sum += a;                  // NaN and infinity survive a sum (a maximum would drop a NaN)
+                        big = fmaxf(big, a);
+                    }
+                bad |= !(sum < 3.0e38f);
+                const float l_tot = swap32_sum(l_run[rb]);
+                tiny |= l_tot > 0.f && swap32_max(big) < kTinyShare * l_tot;
+            }
+        }
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        if (*unfit_note != 0u) {   // the same for every wavefront: run the range again with bf16 weights
+        const bool seen = unfit_note[1] != 0u;
+        if (__builtin_amdgcn_ballot_w64(bad || (seen && tiny)) != 0ull && lane == 0) unfit_note[0] = 1u;
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (unfit_note[0] != 0u) {   // the same for every wavefront: run the range again with bf16 weights
             pass_begin(std::false_type{}, false);
             pass_main(std::false_type{});
         } else {

@@ -402,6 +402,26 @@ def test_verify_values_outside_half_range(ts, variant, kind, hq, hkv, n, t):
     assert_close(lse, rlse, "verify lse, %s values" % kind)
 
 
+@pytest.mark.parametrize("hq,hkv,t", [(32, 8, 64), (40, 8, 64), (4, 4, 100)])
+def test_verify_small_values_beside_normal_ones_keep_their_bits(ts, hq, hkv, t):
+    """Where the second product runs in fp16, values below fp16's normal range (2^-14) sit in subnormals, whose spacing
+    of 2^-24 still holds a bf16 value's eight bits down to 2^-17: columns of such values, next to a column of normal
+    size (so that no row's output is small as a whole and nothing sends the workgroup to its bf16 pass), must come
+    out with their own relative accuracy, not flushed to zero."""
+    n = 1500
+    c = _case(51, hq, hkv, n, t)
+    rng = c["rng"]
+    for arr in (c["v"], c["v_tree"]):
+        small = (rng.integers(16, 255, size=arr.shape).astype(np.float32) * np.float32(2.0 ** -24))   # 2^-20 .. 2^-16, eight bits each
+        small[..., 0] = S.bf16_bits_to_f32(arr[..., 0])                                                # column 0 keeps N(0,1)
+        arr[...] = S.f32_to_bf16_bits(small)
+    parent = _random_parent(rng, t)
+    out, lse, ref, rlse = _verify_both(ts, c, parent)
+    assert_close(out, ref, "verify out, small values beside normal ones")
+    rel = np.abs(out[..., 1:] - ref[..., 1:]) / np.abs(ref[..., 1:])
+    assert float(rel.max()) <= 1e-3, float(rel.max())
+
+
 @pytest.mark.parametrize("kind", ["chain", "star", "deep-wide"])
 def test_verify_wide_trees(ts, kind):
     """Trees of more than 64 nodes (the paper's 40-node tree plus up to 60 retrieved n-gram
