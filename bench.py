@@ -446,9 +446,9 @@ def main():
 
     us_per_layer_step = ms_per_step * 1e3 / n_layers
     us_other = ms_other * 1e3 / n_layers
-    # beyond 128 query rows per KV head (beyond 64 with 16 KV heads or more) the verification pass multiplies fp16 weights with fp16 values
+    # beyond 128 query rows per KV head (beyond 64 with 8 KV heads or more) the verification pass multiplies fp16 weights with fp16 values
     rows = cfg.group * t
-    half = rows > 128 or (rows > 64 and hkv >= 16)
+    half = rows > 128 or (rows > 64 and hkv >= 8)
     dtype = "bf16 inputs, fp32 accumulate" + (" (weights x values of the verification pass in fp16)" if half else "")
     res = {
         "metric": "us per layer-step: chunk scores + top-k + partial-KV attention + tree-verify attention over the full cache",

@@ -190,11 +190,13 @@ bool ts::verify_shape(int n_rows, int n_kv_heads, int variant, VerifyShape *out)
         else *out = VerifyShape{kWide_1x2k4, 64, 1};
     }
     else if (r <= 128) {
-        const bool many_heads = n_kv_heads >= 16;
-        // Many KV heads: each workgroup's range is long either way, and two workgroups of four wavefronts per CU
-        // measured 2-5 % faster than one of twelve; with few heads the extra partials cost more than that.  With
-        // many heads the pass draws the chip's full power (1400 W at ~1.65 GHz for 100 rows on 32 heads x 100K
-        // tokens), where the fp16 second product's smaller matrix work is worth 3 %.
+        // Long ranges on many KV heads: two workgroups of four wavefronts per CU with the fp16 second product.  The pass
+        // then draws the chip's full power (1400 W at 1.7-1.9 GHz for 100 rows on 32 heads x 100K tokens), and the
+        // fp16 product's smaller matrix work and the address arithmetic saved by unrolling over the ring's stages
+        // make it the fastest shape (100 rows on 32 heads x 100K: 310 us against 345 with bf16 weights + residuals;
+        // 128 rows on 8 heads x 65K: 65 against 67).  With few heads the ranges are short and one workgroup of twelve
+        // wavefronts, with half the partials, is faster (96 rows on 2 heads x 16K: 14.7 us against 18.7).
+        const bool many_heads = n_kv_heads >= 8;
         if (variant == 1) *out = many_heads ? VerifyShape{kWide_1x4, 128, 2} : VerifyShape{kWide_1x4h, 128, 2};
         else if (variant == 2) *out = many_heads ? VerifyShape{kWide_1x4k3, 128, 1} : VerifyShape{kWide_1x4, 128, 2};
         else if (variant == 3) *out = VerifyShape{kWide_1x4k2h, 128, 1};

@@ -39,6 +39,7 @@
 // Rows past the end of a range are cut off by the buffer descriptor's byte count; the ring is
 // cleared before a pass so a stage never holds anything but finite values (a masked key adds 0 * V).
 #include <type_traits>
+#include <utility>
 
 #include "ts_device.hpp"
 #include "ts_internal.hpp"
@@ -52,6 +53,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) const bf16x8 *lds_bf16x8_cptr;
+typedef __attribute__((address_space(3))) u32x4 *lds_u32x4_ptr;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 
@@ -80,6 +83,13 @@ __device__ __forceinline__ float swap32_sum(float x)
 {
     u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// f(integral_constant<int, 0>), f(integral_constant<int, 1>), ... in order
+template <int... I, class F>
+__device__ __forceinline__ void for_each_index(std::integer_sequence<int, I...>, F &&f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
 }
 
 // smallest divisor of 16 that is >= ceil(16 / wr): the first 16/LPW wavefronts of a key group issue
@@ -242,6 +252,21 @@ verify_wide_kernel(const VerifyParams p)
             voff[cb] = kVHalf + (4 * hh + i4) * 256 + ((4 * (cb ^ i4) + 2 * mh + (ilo >> 1)) << 4) + ((ilo & 1) << 3);
     }
 
+    // Stage offsets as instruction immediates.  In the steady state of the main loop the stage a step reads is known at
+    // compile time (the loop is unrolled NS times), so an LDS address is a loop-invariant register (LDS base, key group's
+    // first stage, the lane's offset) plus an immediate, and the dozen address additions per step go away.  Possible
+    // where the whole ring lies within the 16-bit offset field of a DS instruction.
+    // (Not where registers are scarce: NS copies of the tile body keep more values alive, and the shapes cut for three
+    // wavefronts per SIMD, or converting four pieces per lane, would spill.)
+    constexpr bool kImmStages = (NS - 1) * KG * kStageBytes + kStageBytes <= 65536 && OCC <= 2 && !(HALF && WR < 4);
+    const uint32_t lds32 = (uint32_t)(uintptr_t)lds + stage0;   // low half of a generic LDS address = LDS offset
+    uint32_t kaddr[8], vaddr[4];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kaddr[ks] = lds32 + koff[ks];
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) vaddr[cb] = lds32 + voff[cb];
+    const uint32_t caddr = lds32 + kVHalf + (wave * 64 + lane) * 16;   // first 16-byte piece this lane converts
+
     const int n_tiles = (range_len + kTileKeys - 1) / kTileKeys;
     const int n_steps = (n_tiles + KG - 1) / KG;   // group tiles per key group (some groups may run one empty)
     // ---- start of a pass over the range (a workgroup makes one, or two if fp16 did not fit) ----
@@ -309,12 +334,17 @@ verify_wide_kernel(const VerifyParams p)
     constexpr int kConvPieces = (kTileKeys * 16 + WR * 64 - 1) / (WR * 64);
     u32x4 conv_raw[kConvPieces], conv_out[kConvPieces];
     uint32_t conv_seen = 0u;   // every bit that was set in any value this lane converted (zero: it saw nothing but zeros)
-    auto conv_load = [&](const unsigned char *stage) {
+    // stage_tag: index of the stage within the key group's ring if known at compile time, else -1 (then `stage` is used)
+    auto conv_load = [&](auto stage_tag, const unsigned char *stage) {
+        constexpr int SI = decltype(stage_tag)::value;
 #pragma unroll
         for (int i = 0; i < kConvPieces; ++i) {
             const int pc = wave * 64 + lane + i * WR * 64;
             const u32x4 z = {0u, 0u, 0u, 0u};
-            conv_raw[i] = pc < kTileKeys * 16 ? *reinterpret_cast<const u32x4 *>(stage + kVHalf + pc * 16) : z;
+            if constexpr (SI >= 0)
+                conv_raw[i] = pc < kTileKeys * 16 ? *reinterpret_cast<lds_u32x4_ptr>(caddr + (SI * KG * kStageBytes + i * WR * 1024)) : z;
+            else
+                conv_raw[i] = pc < kTileKeys * 16 ? *reinterpret_cast<lds_u32x4_ptr>(caddr + ((uint32_t)(stage - lds) - stage0) + i * WR * 1024) : z;
         }
     };
     // word w of piece i: two values converted
@@ -323,35 +353,34 @@ verify_wide_kernel(const VerifyParams p)
         const f32x2 two = {bf16lo_to_f32(x), bf16hi_to_f32(x)};
         conv_out[i][w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(two, f16x2));
     };
-    // rel: offset in the range of the tile's first token
-    auto conv_store = [&](unsigned char *stage, int rel) {
+    // rel: offset in the range of the tile's first token; full_tag: the tile is known to lie wholly inside the range
+    // (the steady state of the main loop), so no row has to be blanked
+    auto conv_store = [&](auto stage_tag, auto full_tag, unsigned char *stage, int rel) {
+        constexpr int SI = decltype(stage_tag)::value;
+        constexpr bool FULL = decltype(full_tag)::value;
         const int left = range_len - rel;
         const int n_valid = left < 0 ? 0 : (left > kTileKeys ? kTileKeys : left);   // wavefront-uniform
 #pragma unroll
         for (int i = 0; i < kConvPieces; ++i) {
             const int pc = wave * 64 + lane + i * WR * 64;
             if (pc < kTileKeys * 16) {
-                u32x4 *at = reinterpret_cast<u32x4 *>(stage + kVHalf + pc * 16);
-                if (n_valid == kTileKeys) {       // the usual case: no row to blank
-                    conv_seen |= conv_raw[i][0] | conv_raw[i][1] | conv_raw[i][2] | conv_raw[i][3];
-                    *at = conv_out[i];
-                } else {
-                    const bool valid = (pc >> 4) < n_valid;
-                    if (valid) conv_seen |= conv_raw[i][0] | conv_raw[i][1] | conv_raw[i][2] | conv_raw[i][3];
-                    const u32x4 z = {0u, 0u, 0u, 0u};
-                    *at = valid ? conv_out[i] : z;
-                }
+                const bool valid = FULL || (pc >> 4) < n_valid;
+                if (valid) conv_seen |= conv_raw[i][0] | conv_raw[i][1] | conv_raw[i][2] | conv_raw[i][3];
+                const u32x4 z = {0u, 0u, 0u, 0u};
+                const u32x4 val = valid ? conv_out[i] : z;
+                if constexpr (SI >= 0) *reinterpret_cast<lds_u32x4_ptr>(caddr + (SI * KG * kStageBytes + i * WR * 1024)) = val;
+                else *reinterpret_cast<lds_u32x4_ptr>(caddr + ((uint32_t)(stage - lds) - stage0) + i * WR * 1024) = val;
             }
         }
     };
     // the whole conversion at once (first tile of a pass; wavefronts without live row blocks)
     auto convert_values = [&](unsigned char *stage, int rel) {
-        conv_load(stage);
+        conv_load(std::integral_constant<int, -1>{}, stage);
 #pragma unroll
         for (int i = 0; i < kConvPieces; ++i)
 #pragma unroll
             for (int w = 0; w < 4; ++w) conv_piece_dword(i, w);
-        conv_store(stage, rel);
+        conv_store(std::integral_constant<int, -1>{}, std::false_type{}, stage, rel);
     };
 
     // One 32-key tile against all of this wavefront's row blocks.  RAGGED tiles (the last one of
@@ -362,9 +391,16 @@ verify_wide_kernel(const VerifyParams p)
 
     // ---- S^T = K . Q^T of one tile --------------------------------------------------------------
     // conv_tag: also convert the values of the tile in conv_stage (first token conv_t0), between the products
-    auto qk_tile = [&](auto live_tag, auto conv_tag, const unsigned char *stage, unsigned char *conv_stage, int conv_rel, auto &sacc) {
+    // stage_tag: index of the tile's stage in the ring when the caller knows it at compile time (then the next stage, the
+    // one converted, is known too), else -1; conv_full_tag: the converted tile lies wholly inside the range
+    auto qk_tile = [&](auto live_tag, auto conv_tag, auto conv_full_tag, auto stage_tag, const unsigned char *stage,
+                       unsigned char *conv_stage, int conv_rel, auto &sacc) {
         constexpr int L = decltype(live_tag)::value;
         constexpr bool CONV = decltype(conv_tag)::value;
+        constexpr int SI = decltype(stage_tag)::value;
+        constexpr int SN = SI >= 0 ? (SI + 1) % NS : -1;
+        const std::integral_constant<int, SN> next_tag{};
+        const uint32_t stage_rel = (uint32_t)(stage - lds) - stage0;   // the stage's offset from the key group's first one (scalar)
 #pragma unroll
         for (int rb = 0; rb < L; ++rb)
 #pragma unroll
@@ -373,8 +409,11 @@ verify_wide_kernel(const VerifyParams p)
         // matrix instructions waits for LDS once, not eight times
         bf16x8 ka[8];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) ka[ks] = *reinterpret_cast<const bf16x8 *>(stage + koff[ks]);
-        if constexpr (CONV) conv_load(conv_stage);
+        for (int ks = 0; ks < 8; ++ks) {
+            if constexpr (SI >= 0) ka[ks] = *reinterpret_cast<lds_bf16x8_cptr>(kaddr[ks] + SI * KG * kStageBytes);
+            else ka[ks] = *reinterpret_cast<lds_bf16x8_cptr>(kaddr[ks] + stage_rel);
+        }
+        if constexpr (CONV) conv_load(next_tag, conv_stage);
         __builtin_amdgcn_sched_barrier(0);
         constexpr int kWords = 4 * kConvPieces;               // 32-bit words this lane converts
         constexpr int kPerSlot = (kWords + 7) / 8;            // ... per matrix instruction of the chain
@@ -392,7 +431,7 @@ verify_wide_kernel(const VerifyParams p)
                 for (int c = ks * kPerSlot; c < (ks + 1) * kPerSlot && c < kWords; ++c) conv_piece_dword(c >> 2, c & 3);
             }
         }
-        if constexpr (CONV) conv_store(conv_stage, conv_rel);
+        if constexpr (CONV) conv_store(next_tag, conv_full_tag, conv_stage, conv_rel);
     };
 
     // Tile sums for the chunk scores (see pv_tile).  The store of a tile's sum waits until just before
@@ -412,10 +451,11 @@ verify_wide_kernel(const VerifyParams p)
     // ---- softmax of one tile's logits and O^T += V^T . P^T ----------------------------------------
     // RAGGED tiles (the last one of a range, every tile of the tree split) mask keys; full tiles
     // carry no masking code.
-    auto pv_tile = [&](auto live_tag, auto ragged_tag, auto half_tag, const unsigned char *stage, int rel, auto &sacc) {
+    auto pv_tile = [&](auto live_tag, auto ragged_tag, auto half_tag, auto stage_tag, const unsigned char *stage, int rel, auto &sacc) {
         constexpr int L = decltype(live_tag)::value;
         constexpr bool RAGGED = decltype(ragged_tag)::value;
         constexpr bool F16 = decltype(half_tag)::value;
+        constexpr int SI = decltype(stage_tag)::value;
 
         // V^T operands: vt[cb][s] = column 32*cb + n32, keys 4*hh + 16*s + 8*(e/4) + e%4 (e = 0..7).
         // The sixteen transposed reads and their wait are one asm block: issued through the
@@ -426,30 +466,36 @@ verify_wide_kernel(const VerifyParams p)
         // products, whose execution covers its LDS latency.
         bf16x8 vt[4][2];
         {
-            const uint32_t sbase = (uint32_t)(uintptr_t)stage;   // low half of a generic LDS address = LDS offset
-            const uint32_t a0 = sbase + voff[0], a1 = sbase + voff[1], a2 = sbase + voff[2], a3 = sbase + voff[3];
+            constexpr int kImm = SI >= 0 ? SI * KG * kStageBytes : 0;   // the stage's offset rides in the instructions
+            uint32_t a0, a1, a2, a3;
+            if constexpr (SI >= 0) {
+                a0 = vaddr[0], a1 = vaddr[1], a2 = vaddr[2], a3 = vaddr[3];
+            } else {
+                const uint32_t stage_rel = (uint32_t)(stage - lds) - stage0;   // scalar
+                a0 = vaddr[0] + stage_rel, a1 = vaddr[1] + stage_rel, a2 = vaddr[2] + stage_rel, a3 = vaddr[3] + stage_rel;
+            }
             u32x2 r[16];
             asm volatile(
-                "ds_read_b64_tr_b16 %0, %16\n\t"
-                "ds_read_b64_tr_b16 %1, %16 offset:2048\n\t"
-                "ds_read_b64_tr_b16 %2, %16 offset:4096\n\t"
-                "ds_read_b64_tr_b16 %3, %16 offset:6144\n\t"
-                "ds_read_b64_tr_b16 %4, %17\n\t"
-                "ds_read_b64_tr_b16 %5, %17 offset:2048\n\t"
-                "ds_read_b64_tr_b16 %6, %17 offset:4096\n\t"
-                "ds_read_b64_tr_b16 %7, %17 offset:6144\n\t"
-                "ds_read_b64_tr_b16 %8, %18\n\t"
-                "ds_read_b64_tr_b16 %9, %18 offset:2048\n\t"
-                "ds_read_b64_tr_b16 %10, %18 offset:4096\n\t"
-                "ds_read_b64_tr_b16 %11, %18 offset:6144\n\t"
-                "ds_read_b64_tr_b16 %12, %19\n\t"
-                "ds_read_b64_tr_b16 %13, %19 offset:2048\n\t"
-                "ds_read_b64_tr_b16 %14, %19 offset:4096\n\t"
-                "ds_read_b64_tr_b16 %15, %19 offset:6144\n\t"
+                "ds_read_b64_tr_b16 %0, %16 offset:%20\n\t"
+                "ds_read_b64_tr_b16 %1, %16 offset:%21\n\t"
+                "ds_read_b64_tr_b16 %2, %16 offset:%22\n\t"
+                "ds_read_b64_tr_b16 %3, %16 offset:%23\n\t"
+                "ds_read_b64_tr_b16 %4, %17 offset:%20\n\t"
+                "ds_read_b64_tr_b16 %5, %17 offset:%21\n\t"
+                "ds_read_b64_tr_b16 %6, %17 offset:%22\n\t"
+                "ds_read_b64_tr_b16 %7, %17 offset:%23\n\t"
+                "ds_read_b64_tr_b16 %8, %18 offset:%20\n\t"
+                "ds_read_b64_tr_b16 %9, %18 offset:%21\n\t"
+                "ds_read_b64_tr_b16 %10, %18 offset:%22\n\t"
+                "ds_read_b64_tr_b16 %11, %18 offset:%23\n\t"
+                "ds_read_b64_tr_b16 %12, %19 offset:%20\n\t"
+                "ds_read_b64_tr_b16 %13, %19 offset:%21\n\t"
+                "ds_read_b64_tr_b16 %14, %19 offset:%22\n\t"
+                "ds_read_b64_tr_b16 %15, %19 offset:%23\n\t"
                 "s_waitcnt lgkmcnt(0)"
                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7]),
                   "=&v"(r[8]), "=&v"(r[9]), "=&v"(r[10]), "=&v"(r[11]), "=&v"(r[12]), "=&v"(r[13]), "=&v"(r[14]), "=&v"(r[15])
-                : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+                : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "n"(kImm), "n"(kImm + 2048), "n"(kImm + 4096), "n"(kImm + 6144)
                 : "memory");
             // r[4*cb + 2*s + x]: keys 16*s + 8*x + 4*hh + (0..3) of column block cb
 #pragma unroll
@@ -657,8 +703,11 @@ verify_wide_kernel(const VerifyParams p)
                 sync_and_refill();
                 convert_values(lds + use_stage, rel_cur);
             }
-            // full tiles first, then the ragged end; the tree split is all ragged
-            auto step = [&](auto ragged_tag) {
+            // One step.  stage_tag: position of the tile's stage in the ring if the caller knows it at compile time (the
+            // unrolled steady state), else -1 and the running use_stage is used; conv_full_tag: the tile after this one
+            // (the one whose values are converted) lies wholly inside the range.
+            auto step = [&](auto ragged_tag, auto conv_full_tag, auto stage_tag) {
+                constexpr int SI = decltype(stage_tag)::value;
                 sync_and_refill();
                 // fp16: the tile after this one has landed too (two are resident); its values are converted
                 // now, between the matrix instructions of this tile's first product
@@ -666,17 +715,31 @@ verify_wide_kernel(const VerifyParams p)
                 if (next_stage >= kRingBytes) next_stage = stage0;
                 if (L > 0) {
                     const unsigned char *stage = lds + use_stage;
-                    qk_tile(live_tag, half_tag, stage, lds + next_stage, rel_cur + KG * kTileKeys, s_cur);
-                    pv_tile(live_tag, ragged_tag, half_tag, stage, rel_cur, s_cur);
+                    qk_tile(live_tag, half_tag, conv_full_tag, stage_tag, stage, lds + next_stage, rel_cur + KG * kTileKeys, s_cur);
+                    pv_tile(live_tag, ragged_tag, half_tag, stage_tag, stage, rel_cur, s_cur);
                 } else if (F16) {
                     convert_values(lds + next_stage, rel_cur + KG * kTileKeys);
                 }
-                use_stage += KG * kStageBytes;
-                if (use_stage >= kRingBytes) use_stage = stage0;
+                if constexpr (SI < 0) {     // (the unrolled loop leaves use_stage where it was: NS steps later)
+                    use_stage += KG * kStageBytes;
+                    if (use_stage >= kRingBytes) use_stage = stage0;
+                }
                 rel_cur += KG * kTileKeys;
             };
-            for (int u = 0; u < n_full_steps; ++u) step(std::false_type{});
-            for (int u = n_full_steps; u < n_steps; ++u) step(std::true_type{});
+            const std::integral_constant<int, -1> any_stage{};
+            // Full tiles first, then the ragged end; the tree split is all ragged.  The steady state -- this tile and the
+            // next both full -- runs NS steps per trip with the stages as compile-time constants.
+            int u = 0;
+            const int n_steady = F16 ? (n_full_steps > 0 ? n_full_steps - 1 : 0) : n_full_steps;
+            if constexpr (kImmStages && L > 0) {
+                for (; u + NS <= n_steady; u += NS) {
+                    for_each_index(std::make_integer_sequence<int, NS>{},
+                                   [&](auto stage_tag) { step(std::false_type{}, std::true_type{}, stage_tag); });
+                }
+            }
+            for (; u < n_steady; ++u) step(std::false_type{}, std::true_type{}, any_stage);
+            for (; u < n_full_steps; ++u) step(std::false_type{}, std::false_type{}, any_stage);
+            for (; u < n_steps; ++u) step(std::true_type{}, std::false_type{}, any_stage);
         };
         if (nrb_live == NRB) run(std::integral_constant<int, NRB>{});
         else run(std::integral_constant<int, NRB - 1>{});   // round-robin dealing: never fewer than NRB-1 unless none at all
