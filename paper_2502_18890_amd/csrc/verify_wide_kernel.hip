@@ -74,6 +74,14 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Largest of three by v_maximum3_f32 (NaN-propagating): written with fmaxf, every operand that comes out of a matrix
+// instruction is first passed through a v_max_f32 x, x that quiets signalling NaNs, one more instruction per value.
+// A NaN logit ends in a NaN weight either way.
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    return __builtin_elementwise_maximum(__builtin_elementwise_maximum(a, b), c);
+}
+
 __device__ __forceinline__ float swap32_max(float x)
 {
     u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -551,10 +559,10 @@ verify_wide_kernel(const VerifyParams p)
                     if (!((vm >> (8 * (e >> 2) + (e & 3))) & 1u)) sacc[rb][e] = -INFINITY;
             }
             // three-input maxima: eight instructions for sixteen values
-            float m = fmaxf(fmaxf(sacc[rb][0], sacc[rb][1]), sacc[rb][2]);
+            float m = max3(sacc[rb][0], sacc[rb][1], sacc[rb][2]);
 #pragma unroll
-            for (int e = 3; e < 15; e += 2) m = fmaxf(fmaxf(m, sacc[rb][e]), sacc[rb][e + 1]);
-            mloc[rb] = fmaxf(m, sacc[rb][15]);
+            for (int e = 3; e < 15; e += 2) m = max3(m, sacc[rb][e], sacc[rb][e + 1]);
+            mloc[rb] = max3(m, sacc[rb][15], sacc[rb][15]);
             moved |= mloc[rb] > m_limit[rb];
         }
         if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {   // some row of this wavefront outgrew its reference
