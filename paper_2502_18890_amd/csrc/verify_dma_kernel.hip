@@ -243,17 +243,17 @@ verify_dma_kernel(const VerifyParams p)
         // exactly the raw logits q.k that Eq. 2 sums; their sum over the tile's valid keys is parked
         // until the next tile's loads are about to be issued (see score_flush), and the merge kernel
         // turns tiles into chunks.
-        if (scoring && t0 < t_end) {
-            float ssum = 0.f;
+        // (This lane's own eight logits are added here, while they are at hand; the cross-lane part of the sum waits
+        // until the second product's matrix instructions have been issued and runs in their shadow.)
+        const bool score_this = scoring && t0 < t_end;
+        float ssum = 0.f;
+        if (score_this) {
             const uint32_t ok = RAGGED ? (uint32_t)((t_end - t0 >= 32 ? 0xffffffffull : ((1ull << (t_end - t0)) - 1ull)) >> (quad * 4)) : 0xffffffffu;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float v = sacc[0][e >> 2][e & 3];
                 ssum += (!RAGGED || ((ok >> ((e >> 2) * 16 + (e & 3))) & 1u)) ? v : 0.f;
             }
-            ssum = xrow_sum(ssum);                                   // the four lanes that share row j
-            score_parked = row16_sum(j < p.group ? ssum : 0.f);     // the group's heads
-            score_parked_tile = t0 >> 5;
         }
         // 8 keys x 4 consecutive columns per read, regrouped into one column x 8 keys per operand
         bf16x8 av[2][4];
@@ -350,6 +350,11 @@ verify_dma_kernel(const VerifyParams p)
                 for (int i = 0; i < 4; ++i)
                     oacc[rb][dg][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[dg][i], p_lo[rb & 1], oacc[rb][dg][i], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
+        }
+        if (score_this) {
+            ssum = xrow_sum(ssum);                                   // the four lanes that share row j
+            score_parked = row16_sum(j < p.group ? ssum : 0.f);     // the group's heads
+            score_parked_tile = t0 >> 5;
         }
     };
 

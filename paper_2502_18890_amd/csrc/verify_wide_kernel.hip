@@ -519,17 +519,17 @@ verify_wide_kernel(const VerifyParams p)
         // in wavefront 0 of every key group) hold exactly the raw logits q.k that Eq. 2 sums; their sum
         // over the tile's valid keys is parked until the next tile's loads are about to be issued (see
         // score_flush), and the merge kernel turns tiles into chunks.
-        if (L > 0 && scoring && rel < range_len) {
-            float ssum = 0.f;
+        // (This lane's own sixteen logits are added here, while they are at hand; the cross-lane part of the sum waits
+        // until the second product's matrix instructions have been issued and runs in their shadow.)
+        const bool score_this = L > 0 && scoring && rel < range_len;
+        float ssum = 0.f;
+        if (score_this) {
             const uint32_t ok = RAGGED ? (uint32_t)((range_len - rel >= 32 ? 0xffffffffull : ((1ull << (range_len - rel)) - 1ull)) >> (hh * 4)) : 0xffffffffu;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const float v = sacc[0][e];
                 ssum += (!RAGGED || ((ok >> (8 * (e >> 2) + (e & 3))) & 1u)) ? v : 0.f;
             }
-            ssum = swap32_sum(ssum);                                     // the two lanes that share row n32
-            score_parked = row16_sum(n32 < p.group ? ssum : 0.f);       // the group's heads (group <= 8: one 16-lane row)
-            score_parked_tile = rel >> 5;
         }
 
         // m_run is a reference point, not necessarily the exact running maximum: the accumulators are
@@ -679,6 +679,11 @@ verify_wide_kernel(const VerifyParams p)
                         oacc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[cb][s], p_lo[s], oacc[rb][cb], 0, 0, 0);
                     }
             }
+        }
+        if (score_this) {
+            ssum = swap32_sum(ssum);                                     // the two lanes that share row n32
+            score_parked = row16_sum(n32 < p.group ? ssum : 0.f);       // the group's heads (group <= 8: one 16-lane row)
+            score_parked_tile = rel >> 5;
         }
     };
 
