@@ -172,7 +172,7 @@ int ts_partial_kv_attn_static(const ts_kv_view *kv, const void *q, int n_q_heads
  *   out             fp32 [n_tree][n_q_heads][128]
  *   lse             fp32 [n_tree][n_q_heads]; nullable
  *   workspace       >= ts_workspace_bytes(TS_OP_TREE_VERIFY, ...) bytes, 256-byte aligned
- * n_tree: 1..TS_MAX_TREE.  kv->n_tokens may be 0 (then kv->k, kv->v may be NULL).  scale must be
+ * n_tree: 1..TS_MAX_TREE.  kv->n_tokens may be 0 (then kv->k, kv->v may be NULL) and must be below 2^31.  scale must be
  * positive and below 2e38 (TS_ERR_UNSUPPORTED otherwise).
  * Errors: TS_ERR_TREE for a malformed parent array; the others as above.
  */

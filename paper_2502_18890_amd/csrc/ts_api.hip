@@ -105,7 +105,7 @@ bool plan_verify(int n_q_heads, int n_kv_heads, int64_t n_tokens, int n_tree, bo
     const int group = n_q_heads / n_kv_heads;
     pl->n_rows = group * n_tree;
     pl->n_rows_pad = (pl->n_rows + 15) / 16 * 16;
-    if (!ts::verify_shape(pl->n_rows, n_kv_heads, g_tune.verify_variant.load(std::memory_order_relaxed), &pl->shape)) return false;
+    if (!ts::verify_shape(pl->n_rows, n_kv_heads, n_tokens, g_tune.verify_variant.load(std::memory_order_relaxed), &pl->shape)) return false;
     if (const int forced = g_tune.verify_kernel.load(std::memory_order_relaxed)) {
         const ts::VerifyKernelInfo info = ts::verify_kernel_info(forced - 1);
         if (info.max_rows >= pl->n_rows) pl->shape = ts::VerifyShape{forced - 1, (pl->n_rows + 31) / 32 * 32, info.wg_per_cu};
@@ -170,7 +170,7 @@ bool partial_chunk_ok(int chunk_size) { return chunk_size >= 16 && chunk_size <=
 // shapes; variant 1..3 select alternatives where there are any (all produce the same results):
 // 1 swaps the precision of the second product (fp16 where the default is bf16 + residual and
 // the other way round), 2 and 3 other workgroup shapes.
-bool ts::verify_shape(int n_rows, int n_kv_heads, int variant, VerifyShape *out)
+bool ts::verify_shape(int n_rows, int n_kv_heads, int64_t n_tokens, int variant, VerifyShape *out)
 {
     if (n_rows < 1 || n_rows > TS_MAX_GROUP * TS_MAX_TREE) return false;
     if (variant == 0 && n_rows <= 16) {
@@ -190,17 +190,19 @@ bool ts::verify_shape(int n_rows, int n_kv_heads, int variant, VerifyShape *out)
         else *out = VerifyShape{kWide_1x2k4, 64, 1};
     }
     else if (r <= 128) {
-        // Long ranges on many KV heads: two workgroups of four wavefronts per CU with the fp16 second product.  The pass
-        // then draws the chip's full power (1400 W at 1.7-1.9 GHz for 100 rows on 32 heads x 100K tokens), and the
-        // fp16 product's smaller matrix work and the address arithmetic saved by unrolling over the ring's stages
-        // make it the fastest shape (100 rows on 32 heads x 100K: 310 us against 345 with bf16 weights + residuals;
-        // 128 rows on 8 heads x 65K: 65 against 67).  With few heads the ranges are short and one workgroup of twelve
-        // wavefronts, with half the partials, is faster (96 rows on 2 heads x 16K: 14.7 us against 18.7).
+        // With 8 or more KV heads the pass draws the chip's full power (1400 W at 1.7-1.9 GHz for 100 rows on 32 heads x
+        // 100K tokens), and the fp16 second product's smaller matrix work, with the address arithmetic saved by
+        // unrolling over the ring's stages, is the fastest: two workgroups of four wavefronts per CU where each
+        // workgroup's range is long (100 rows on 32 heads x 100K: 308 us against 345 with bf16 weights + residuals,
+        // 325 with one workgroup of eight), one workgroup of two key groups x four wavefronts, with half the partials to
+        // write and merge, where it is short (128 rows on 8 heads x 65K: whole call 71 us against 74).  With few heads
+        // one workgroup of three key groups with bf16 weights is faster (96 rows on 2 heads x 16K: 14.9 us against 17.2).
         const bool many_heads = n_kv_heads >= 8;
+        const bool long_ranges = n_tokens * n_kv_heads / 512 >= 4096;   // tokens per workgroup at two workgroups per CU
         if (variant == 1) *out = many_heads ? VerifyShape{kWide_1x4, 128, 2} : VerifyShape{kWide_1x4h, 128, 2};
         else if (variant == 2) *out = many_heads ? VerifyShape{kWide_1x4k3, 128, 1} : VerifyShape{kWide_1x4, 128, 2};
-        else if (variant == 3) *out = VerifyShape{kWide_1x4k2h, 128, 1};
-        else if (many_heads) *out = VerifyShape{kWide_1x4h, 128, 2};
+        else if (variant == 3) *out = many_heads && !long_ranges ? VerifyShape{kWide_1x4h, 128, 2} : VerifyShape{kWide_1x4k2h, 128, 1};
+        else if (many_heads) *out = long_ranges ? VerifyShape{kWide_1x4h, 128, 2} : VerifyShape{kWide_1x4k2h, 128, 1};
         else *out = VerifyShape{kWide_1x4k3, 128, 1};
     } else if (r <= 256) {
         if (variant == 1) *out = VerifyShape{kWide_1x8, 256, 1};
@@ -426,6 +428,7 @@ static int verify_call(const ts_kv_view *kv, const void *q_tree, int n_q_heads,
     if ((rc = check_heads(n_q_heads, kv->n_kv_heads, &group)) != TS_OK) return rc;
     if (n_tree < 1) return TS_ERR_SHAPE;
     if (n_tree > TS_MAX_TREE || !scale_ok(scale)) return TS_ERR_UNSUPPORTED;
+    if (kv->n_tokens > 0x7fffffffLL) return TS_ERR_UNSUPPORTED;   // the kernels keep positions inside a range in 32 bits
     for (int i = 0; i < n_tree; ++i)
         if (parent[i] < -1 || parent[i] >= i) return TS_ERR_TREE;
     if (!aligned16(q_tree) || !aligned16(k_tree) || !aligned16(v_tree) || (out && !aligned16(out))) return TS_ERR_ALIGN;

@@ -82,7 +82,7 @@ struct VerifyShape {
     int rows_per_wg;   // rows covered by one workgroup (multiple of 32 for the wide kernel)
     int wg_per_cu;     // workgroups of this shape one CU holds at a time
 };
-bool verify_shape(int n_rows, int n_kv_heads, int variant, VerifyShape *out);   // false if n_rows is out of range
+bool verify_shape(int n_rows, int n_kv_heads, int64_t n_tokens, int variant, VerifyShape *out);   // false if n_rows is out of range
 hipError_t launch_verify_narrow(const VerifyParams &p, int kernel_id, hipStream_t stream);
 hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t stream);
 

@@ -199,7 +199,7 @@ verify_wide_kernel(const VerifyParams p)
     // Load instruction ii (0..15) of a tile fills LDS block ii: K rows 4ii..4ii+3 for ii < 8,
     // V rows 4(ii-8).. for ii >= 8.  Wavefront `wave` of a key group issues ii = wave*LPW ..
     // wave*LPW+LPW-1 of that group's tiles if those are < 16, else nothing.  Group tile number u of
-    // key group kg is tile u*KG + kg of the range and lives in stage (u % NS)*KG + kg.
+    // key group kg is tile u*KG + kg of the range and lives in stage kg*NS + u % NS.
     const bool loader = wave * LPW < 16;
     uint32_t goff[LPW];
 #pragma unroll
@@ -212,8 +212,8 @@ verify_wide_kernel(const VerifyParams p)
     // Tiles are issued and consumed strictly in order, so both sides keep running cursors (a few
     // scalar additions per step) instead of recomputing addresses from the tile number: the scalar
     // unit is shared by the whole CU and this code sits on every wavefront's path after the barrier.
-    constexpr uint32_t kRingBytes = NS * KG * kStageBytes;
-    const uint32_t stage0 = kg * kStageBytes;
+    const uint32_t stage0 = kg * NS * kStageBytes;       // a key group's NS stages lie next to each other
+    const uint32_t stage_end = stage0 + NS * kStageBytes;
     const int64_t tile_elems = (int64_t)KG * kTileKeys * tstride;      // elements between consecutive group tiles
     const uint16_t *kfill, *vfill;
     int fill_rel;              // offset in the range of the first row of the next tile to fill
@@ -241,8 +241,8 @@ verify_wide_kernel(const VerifyParams p)
             kfill += tile_elems;     // past the range the descriptor covers 0 bytes, so the base is never dereferenced
             vfill += tile_elems;
             fill_rel += KG * kTileKeys;
-            fill_stage += KG * kStageBytes;
-            if (fill_stage >= kRingBytes) fill_stage = stage0;
+            fill_stage += kStageBytes;
+            if (fill_stage >= stage_end) fill_stage = stage0;
         }
     };
 
@@ -266,7 +266,7 @@ verify_wide_kernel(const VerifyParams p)
     // where the whole ring lies within the 16-bit offset field of a DS instruction.
     // (Not where registers are scarce: NS copies of the tile body keep more values alive, and the shapes cut for three
     // wavefronts per SIMD, or converting four pieces per lane, would spill.)
-    constexpr bool kImmStages = (NS - 1) * KG * kStageBytes + kStageBytes <= 65536 && OCC <= 2 && !(HALF && WR < 4);
+    constexpr bool kImmStages = NS * kStageBytes <= 65536 && OCC <= 2 && !(HALF && WR < 4);
     const uint32_t lds32 = (uint32_t)(uintptr_t)lds + stage0;   // low half of a generic LDS address = LDS offset
     uint32_t kaddr[8], vaddr[4];
 #pragma unroll
@@ -350,7 +350,7 @@ verify_wide_kernel(const VerifyParams p)
             const int pc = wave * 64 + lane + i * WR * 64;
             const u32x4 z = {0u, 0u, 0u, 0u};
             if constexpr (SI >= 0)
-                conv_raw[i] = pc < kTileKeys * 16 ? *reinterpret_cast<lds_u32x4_ptr>(caddr + (SI * KG * kStageBytes + i * WR * 1024)) : z;
+                conv_raw[i] = pc < kTileKeys * 16 ? *reinterpret_cast<lds_u32x4_ptr>(caddr + (SI * kStageBytes + i * WR * 1024)) : z;
             else
                 conv_raw[i] = pc < kTileKeys * 16 ? *reinterpret_cast<lds_u32x4_ptr>(caddr + ((uint32_t)(stage - lds) - stage0) + i * WR * 1024) : z;
         }
@@ -376,7 +376,7 @@ verify_wide_kernel(const VerifyParams p)
                 if (valid) conv_seen |= conv_raw[i][0] | conv_raw[i][1] | conv_raw[i][2] | conv_raw[i][3];
                 const u32x4 z = {0u, 0u, 0u, 0u};
                 const u32x4 val = valid ? conv_out[i] : z;
-                if constexpr (SI >= 0) *reinterpret_cast<lds_u32x4_ptr>(caddr + (SI * KG * kStageBytes + i * WR * 1024)) = val;
+                if constexpr (SI >= 0) *reinterpret_cast<lds_u32x4_ptr>(caddr + (SI * kStageBytes + i * WR * 1024)) = val;
                 else *reinterpret_cast<lds_u32x4_ptr>(caddr + ((uint32_t)(stage - lds) - stage0) + i * WR * 1024) = val;
             }
         }
@@ -418,7 +418,7 @@ verify_wide_kernel(const VerifyParams p)
         bf16x8 ka[8];
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            if constexpr (SI >= 0) ka[ks] = *reinterpret_cast<lds_bf16x8_cptr>(kaddr[ks] + SI * KG * kStageBytes);
+            if constexpr (SI >= 0) ka[ks] = *reinterpret_cast<lds_bf16x8_cptr>(kaddr[ks] + SI * kStageBytes);
             else ka[ks] = *reinterpret_cast<lds_bf16x8_cptr>(kaddr[ks] + stage_rel);
         }
         if constexpr (CONV) conv_load(next_tag, conv_stage);
@@ -474,7 +474,7 @@ verify_wide_kernel(const VerifyParams p)
         // products, whose execution covers its LDS latency.
         bf16x8 vt[4][2];
         {
-            constexpr int kImm = SI >= 0 ? SI * KG * kStageBytes : 0;   // the stage's offset rides in the instructions
+            constexpr int kImm = SI >= 0 ? SI * kStageBytes : 0;   // the stage's offset rides in the instructions
             uint32_t a0, a1, a2, a3;
             if constexpr (SI >= 0) {
                 a0 = vaddr[0], a1 = vaddr[1], a2 = vaddr[2], a3 = vaddr[3];
@@ -724,8 +724,8 @@ verify_wide_kernel(const VerifyParams p)
                 sync_and_refill();
                 // fp16: the tile after this one has landed too (two are resident); its values are converted
                 // now, between the matrix instructions of this tile's first product
-                uint32_t next_stage = use_stage + KG * kStageBytes;
-                if (next_stage >= kRingBytes) next_stage = stage0;
+                uint32_t next_stage = use_stage + kStageBytes;
+                if (next_stage >= stage_end) next_stage = stage0;
                 if (L > 0) {
                     const unsigned char *stage = lds + use_stage;
                     qk_tile(live_tag, half_tag, conv_full_tag, stage_tag, stage, lds + next_stage, rel_cur + KG * kTileKeys, s_cur);
@@ -734,8 +734,8 @@ verify_wide_kernel(const VerifyParams p)
                     convert_values(lds + next_stage, rel_cur + KG * kTileKeys);
                 }
                 if constexpr (SI < 0) {     // (the unrolled loop leaves use_stage where it was: NS steps later)
-                    use_stage += KG * kStageBytes;
-                    if (use_stage >= kRingBytes) use_stage = stage0;
+                    use_stage += kStageBytes;
+                    if (use_stage >= stage_end) use_stage = stage0;
                 }
                 rel_cur += KG * kTileKeys;
             };

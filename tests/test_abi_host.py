@@ -127,6 +127,7 @@ def test_attention_calls_reject_bad_arguments(lib, binding):
                                        par, len(parent) if parent is not None else 4, scale, out_, None, ws_, wsb, None)
     assert tv([-1, 0], scale=0.0) == TS_ERR_UNSUPPORTED and tv([-1, 0], scale=-0.5) == TS_ERR_UNSUPPORTED
     assert tv([-1, 0], scale=float("nan")) == TS_ERR_UNSUPPORTED and tv([-1, 0], scale=2.5e38) == TS_ERR_UNSUPPORTED
+    assert tv([-1, 0], view=_view(binding, n=1 << 31)) == TS_ERR_UNSUPPORTED
     assert tv(None) == TS_ERR_NULL
     assert tv([-1, 0], kt=None) == TS_ERR_NULL
     assert tv([0, 0]) == TS_ERR_TREE            # a node cannot be its own parent
