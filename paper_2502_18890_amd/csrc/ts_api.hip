@@ -207,7 +207,8 @@ bool ts::verify_shape(int n_rows, int n_kv_heads, int64_t n_tokens, int variant,
     } else if (r <= 256) {
         if (variant == 1) *out = VerifyShape{kWide_1x8, 256, 1};
         else if (variant == 2) *out = VerifyShape{kWide_2x4, 256, 1};
-        else *out = VerifyShape{kWide_1x8h, 256, 1};
+        else if (variant == 3) *out = VerifyShape{kWide_1x8h, 256, 1};
+        else *out = VerifyShape{kWide_1x8h4, 256, 1};   // four stages: their offsets ride in the instructions (3 % over six stages)
     } else {
         if (variant == 1) *out = r <= 320 ? VerifyShape{kWide_1x10, 320, 1} : VerifyShape{kWide_1x12, 384, 1};
         else *out = r <= 320 ? VerifyShape{kWide_1x10h, 320, 1} : VerifyShape{kWide_1x12h, 384, 1};
@@ -227,7 +228,7 @@ ts::VerifyKernelInfo ts::verify_kernel_info(int id)
         case kWide_1x2k4: return {64, 1};
         case kWide_1x4: case kWide_1x4h: return {128, 2};
         case kWide_1x4k3: case kWide_1x4k2h: return {128, 1};
-        case kWide_2x4: case kWide_1x8: case kWide_1x8h: return {256, 1};
+        case kWide_2x4: case kWide_1x8: case kWide_1x8h: case kWide_1x8h4: return {256, 1};
         case kWide_1x10: case kWide_1x10h: return {320, 1};
         case kWide_1x12: case kWide_1x12h: return {384, 1};
         case kWide_2x2: return {128, 2};

@@ -72,6 +72,7 @@ enum VerifyKernelId {
     kWide_2x2,        // two workgroups of two wavefronts per CU
     kWide_2x2k2,      // two key groups
     kWide_2x2k2b,     // ... with a three-stage ring
+    kWide_1x8h4,      // 1x8h with a four-stage ring (stage offsets as immediates)
     kVerifyKernelCount
 };
 // rows one workgroup of a kernel covers at most, and workgroups of it a CU holds (0 rows: no such kernel)

@@ -922,6 +922,7 @@ hipError_t launch_verify_wide(const VerifyParams &p, int kernel_id, hipStream_t 
         case kWide_2x2: return launch_one<2, 2, 1, 4, 1, false>(p, stream);
         case kWide_2x2k2: return launch_one<2, 2, 2, 4, 1, false>(p, stream);
         case kWide_2x2k2b: return launch_one<2, 2, 2, 3, 1, false>(p, stream);
+        case kWide_1x8h4: return launch_one<1, 8, 1, 4, 2, false, true>(p, stream);
         default: return hipErrorInvalidValue;
     }
 }

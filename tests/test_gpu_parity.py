@@ -345,7 +345,7 @@ def test_verify_kernel_variants(ts, variant, hq, hkv, n, t):
 # every instantiation of the two verification kernels, by its position in the library's list of kernel shapes, with the
 # largest number of query rows per KV head it covers (the "verify_kernel" override falls back to the default shape when
 # a kernel cannot cover the rows, so each case below really runs the kernel it names)
-KERNEL_ROWS = [16, 32, 32, 32, 64, 64, 128, 128, 256, 256, 320, 384, 64, 128, 128, 256, 320, 384, 128, 128, 128]
+KERNEL_ROWS = [16, 32, 32, 32, 64, 64, 128, 128, 256, 256, 320, 384, 64, 128, 128, 256, 320, 384, 128, 128, 128, 256]
 ROW_SHAPES = {16: [(4, 4, 16), (2, 2, 5)], 32: [(8, 4, 16), (4, 4, 23)], 64: [(8, 2, 16), (12, 4, 17)], 128: [(32, 8, 32), (4, 4, 100), (8, 2, 27)],
               256: [(32, 8, 64), (8, 2, 51)], 320: [(40, 8, 64), (10, 2, 57)], 384: [(48, 8, 64), (6, 1, 61)]}
 
