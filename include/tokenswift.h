@@ -48,7 +48,7 @@ typedef enum {
 #define TS_HEAD_DIM 128
 #define TS_MAX_TREE 128       /* tree nodes per call (one 128-bit ancestor mask per node) */
 #define TS_MAX_GROUP 8        /* query heads per KV head */
-#define TS_MAX_CHUNKS (1 << 20)  /* chunks per KV head that ts_topk_chunks can rank */
+#define TS_MAX_CHUNKS (1 << 20)  /* chunks per KV head that ts_topk_chunks can rank; also the longest chunk list (n_sel) */
 #define TS_MAX_TOPK 8192      /* chunks per KV head that ts_topk_chunks can select (k) */
 #define TS_MAX_STRIDE_TOKEN (1 << 24) /* largest stride_token, in elements (32 MiB between token rows) */
 #define TS_STATIC_SCRATCH_BYTES (4 << 20) /* fixed scratch of ts_partial_kv_attn_static, per GPU */
@@ -134,7 +134,8 @@ int ts_topk_chunks(const float *scores, int n_kv_heads, int n_chunks, int n_sink
  *   lse        fp32 [n_q_heads], natural-log sum of exponentials of the scaled logits; nullable
  *   workspace  >= ts_workspace_bytes(TS_OP_PARTIAL_ATTN, ...) bytes, 256-byte aligned
  * chunk_size: multiple of 16, 16..1024.  scale must be positive and below 2e38, so that scale * log2(e)
- * is finite (TS_ERR_UNSUPPORTED otherwise).  Errors as above plus n_sel < 1.
+ * is finite (TS_ERR_UNSUPPORTED otherwise).  Errors as above plus n_sel < 1 (TS_ERR_SHAPE) and
+ * n_sel > TS_MAX_CHUNKS (TS_ERR_UNSUPPORTED).
  */
 int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
                        const int32_t *chunk_idx, int n_sel, int chunk_size, float scale,
@@ -263,7 +264,7 @@ int ts_chunk_list_admit(int32_t *chunk_idx, int n_kv_heads, int n_sel, int n_sin
  * ts_partial_kv_attn does not need this copy, it reads the chunks in place).
  *   k_out, v_out  bf16 [n_kv_heads][n_sel * chunk_size][128]; rows of a chunk past the end of
  *                 the cache are zero-filled
- * chunk_size: multiple of 16, 16..1024.
+ * chunk_size: multiple of 16, 16..1024; 1 <= n_sel <= TS_MAX_CHUNKS.
  */
 int ts_gather_chunks(const ts_kv_view *kv, const int32_t *chunk_idx, int n_sel, int chunk_size,
                      void *k_out, void *v_out, void *stream);

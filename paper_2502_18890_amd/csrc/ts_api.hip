@@ -288,7 +288,7 @@ size_t ts_workspace_bytes(int op, int n_q_heads, int n_kv_heads, int64_t n_token
         return pl.bytes;
     }
     if (op == TS_OP_PARTIAL_ATTN) {
-        if (n_sel < 1 || !partial_chunk_ok(chunk_size)) return 0;
+        if (n_sel < 1 || n_sel > TS_MAX_CHUNKS || !partial_chunk_ok(chunk_size)) return 0;
         PartialPlan pl;
         plan_partial(n_q_heads, n_kv_heads, n_sel, chunk_size, &pl);
         return pl.bytes;
@@ -351,7 +351,7 @@ int ts_partial_kv_attn(const ts_kv_view *kv, const void *q, int n_q_heads,
     int group = 0;
     if ((rc = check_heads(n_q_heads, kv->n_kv_heads, &group)) != TS_OK) return rc;
     if (n_sel < 1) return TS_ERR_SHAPE;
-    if (!partial_chunk_ok(chunk_size) || !scale_ok(scale)) return TS_ERR_UNSUPPORTED;
+    if (n_sel > TS_MAX_CHUNKS || !partial_chunk_ok(chunk_size) || !scale_ok(scale)) return TS_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(out)) return TS_ERR_ALIGN;
     PartialPlan pl;
     plan_partial(n_q_heads, kv->n_kv_heads, n_sel, chunk_size, &pl);
@@ -405,7 +405,7 @@ int ts_partial_kv_attn_static(const ts_kv_view *kv, const void *q, int n_q_heads
     int group = 0;
     if ((rc = check_heads(n_q_heads, kv->n_kv_heads, &group)) != TS_OK) return rc;
     if (n_sel < 1) return TS_ERR_SHAPE;
-    if (!partial_chunk_ok(chunk_size) || !scale_ok(scale)) return TS_ERR_UNSUPPORTED;
+    if (n_sel > TS_MAX_CHUNKS || !partial_chunk_ok(chunk_size) || !scale_ok(scale)) return TS_ERR_UNSUPPORTED;
     PartialPlan pl;
     plan_partial(n_q_heads, kv->n_kv_heads, n_sel, chunk_size, &pl);
     if (pl.bytes > kScratchBytes) return TS_ERR_WORKSPACE;    // beyond the fixed scratch: use ts_partial_kv_attn
@@ -589,7 +589,7 @@ int ts_gather_chunks(const ts_kv_view *kv, const int32_t *chunk_idx, int n_sel, 
     if (rc != TS_OK) return rc;
     if (!chunk_idx || !k_out || !v_out) return TS_ERR_NULL;
     if (n_sel < 1) return TS_ERR_SHAPE;
-    if (!partial_chunk_ok(chunk_size)) return TS_ERR_UNSUPPORTED;
+    if (n_sel > TS_MAX_CHUNKS || !partial_chunk_ok(chunk_size)) return TS_ERR_UNSUPPORTED;
     if (!aligned16(k_out) || !aligned16(v_out)) return TS_ERR_ALIGN;
     if ((int64_t)n_sel * chunk_size / 16 > 0x7fffffffLL) return TS_ERR_UNSUPPORTED;
     ts::GatherParams p;

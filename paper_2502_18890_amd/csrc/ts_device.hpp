@@ -31,15 +31,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     return __builtin_bit_cast(uint32_t, y);
 }
 
-// element-wise maximum of two pairs of unsigned 16-bit values
-__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
-{
-    typedef __attribute__((ext_vector_type(2))) unsigned short u16x2;
-    const u16x2 x = __builtin_bit_cast(u16x2, a), y = __builtin_bit_cast(u16x2, b);
-    const u16x2 m = {x[0] > y[0] ? x[0] : y[0], x[1] > y[1] ? x[1] : y[1]};
-    return __builtin_bit_cast(uint32_t, m);
-}
-
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 

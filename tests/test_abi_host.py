@@ -110,6 +110,7 @@ def test_attention_calls_reject_bad_arguments(lib, binding):
     assert pa(idx_=None) == TS_ERR_NULL and pa(out_=None) == TS_ERR_NULL and pa(q_=None) == TS_ERR_NULL
     assert pa(view=_view(binding, v=None)) == TS_ERR_NULL
     assert pa(n_sel=0) == TS_ERR_SHAPE
+    assert pa(n_sel=(1 << 20) + 1) == TS_ERR_UNSUPPORTED          # the segment count would leave 32 bits
     assert pa(chunk=24) == TS_ERR_UNSUPPORTED and pa(chunk=8) == TS_ERR_UNSUPPORTED
     assert pa(ws_=None) == TS_ERR_WORKSPACE and pa(wsb=16) == TS_ERR_WORKSPACE
     assert pa(ws_=ws + 16) == TS_ERR_WORKSPACE                  # not 256-byte aligned
