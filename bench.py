@@ -361,6 +361,12 @@ def main():
     ms_per_step = timed(run_step, args.steps)
     wall = time.perf_counter() - wall0
     ms_other = timed(other_step, max(2, args.steps // 2))
+    # the same step replayed from a HIP graph (no launch gaps between the five kernels of a layer), beside the eager figure
+    graph_us = None
+    if not args.graph:
+        g = w.graph_of(step)
+        graph_us = timed(g.replay, args.steps) * 1e3 / n_layers
+        del g
 
     reps = max(2, args.steps // 4)
 
@@ -462,6 +468,7 @@ def main():
                  "three passes: ts_tree_verify_attn_scored (verification; its query-key products of tree node 0 also give the "
                  "chunk scores, same values as ts_chunk_scores for that query), ts_topk_chunks, ts_partial_kv_attn"),
         # the step that assumes nothing about which query ranks the cache: the scores are a pass of their own
+        "value_graph_replay": round(us_per_layer_step if args.graph else graph_us, 3),
         "value_no_reading": round(us_per_layer_step if args.four_pass else us_other, 3),
         "value_scores_left_to_verification": round(us_other if args.four_pass else us_per_layer_step, 3),
         "reading": "value_scores_left_to_verification holds if the query that ranks the cache is the verification pass's query "
