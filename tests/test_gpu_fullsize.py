@@ -4,7 +4,8 @@ and the fp64 oracle checks every chunk score (from the scoring pass and from the
 leaves them), the selection (bit-exact from the GPU's scores),
 the whole partial-attention output, and every row of the tree verification (output and lse).  One more case runs
 the verification alone at the paper's own width: the 40-node [1,3,3,3] tree plus 20 retrieved 4-grams that share its
-root (Sec. 3.2 "Token Reutilization", App. E; 100 tokens) over the 100000-token MHA layer."""
+root (Sec. 3.2 "Token Reutilization", App. E; 100 tokens) over the 100000-token MHA layer, and over the 65536-token
+layer of the 4-way GQA shape (400 query rows per KV head)."""
 import numpy as np
 import pytest
 
@@ -75,11 +76,14 @@ def paper_width_tree():
     return np.asarray(parent, dtype=np.int32)
 
 
-def test_full_size_paper_width_verification():
+@pytest.mark.parametrize("ci", [3, 2])
+def test_full_size_paper_width_verification(ci):
+    """The paper's widest verification input (Sec. 3.2: the 40-node tree plus 20 retrieved 4-grams, 100 tokens) over a full
+    cache: 100 query rows per KV head on the MHA shape, 400 on the 4-way GQA shape (two row tiles)."""
     import torch
     import paper_2502_18890_amd as ts
 
-    cfg = S.CONFIGS[3]
+    cfg = S.CONFIGS[ci]
     parent = paper_width_tree()
     t = len(parent)
     assert t == 100
@@ -93,6 +97,6 @@ def test_full_size_paper_width_verification():
     bits = S.torch_bf16_to_bits
     k, v = bits(x["k"]), bits(x["v"])
     ref_v, ref_lse_v = oracle.tree_verify(bits(x["q_tree"]), k, v, bits(x["k_tree"]), bits(x["v_tree"]), parent, cfg.scale)
-    assert_close(out_v.cpu().numpy(), ref_v, "verify out, 100 tree tokens x 100000 cached")
-    assert_close(lse_v.cpu().numpy(), ref_lse_v, "verify lse, 100 tree tokens x 100000 cached")
+    assert_close(out_v.cpu().numpy(), ref_v, "verify out, 100 tree tokens x %d cached" % cfg.n_tokens)
+    assert_close(lse_v.cpu().numpy(), ref_lse_v, "verify lse, 100 tree tokens x %d cached" % cfg.n_tokens)
     assert_close(sc_s.cpu().numpy(), oracle.chunk_scores(bits(x["q_tree"])[0], k, cfg.chunk, cfg.scale), "scores left by it")
