@@ -513,7 +513,7 @@ def main():
 
     if args.config is None and not args.tree and not args.layers and not args.splits and not args.zero_cache:
         # the other workloads in brief: the paper's verification width on the headline caches, then the two large
-        # GQA shapes; the two small shapes eager and as a graph replay
+        # GQA shapes (the first of them also at the paper's verification width); the two small shapes eager and as a graph replay
         steps = max(4, args.steps // 2)
         others = [Workload(cfg, dev, 0, 100, layers=layers).brief(steps, 1, args.kernel_loops)]
         del w, layers, x0
@@ -521,6 +521,8 @@ def main():
         for cj in (2, 4):
             wj = Workload(S.CONFIGS[cj], dev)
             others.append(wj.brief(steps, 1, args.kernel_loops))
+            if cj == 2:   # the paper's verification width on a GQA shape: 400 query rows per KV head, two row tiles
+                others.append(Workload(S.CONFIGS[cj], dev, 0, 100, layers=wj.layers).brief(steps, 1, args.kernel_loops))
             del wj
             torch.cuda.empty_cache()
         res["workloads"] = others
