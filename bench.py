@@ -244,11 +244,18 @@ class Workload:
         return lambda: [fn(x) for x in self.layers]
 
     def split_kernel_us(self, scored, loops):
-        """Average duration of the verification pass's split kernel alone over `loops` sweeps of the layers
-        (HIP events on the launch stream); the first, untimed sweep brings the chip under the same load."""
+        """Average duration of the verification pass's split kernel alone over at least `loops` sweeps of the layers and at
+        least 20 ms (HIP events on the launch stream).  Untimed sweeps come first until the chip has run this kernel for
+        40 ms: the power limit sets the clock of the wide passes, and for the first milliseconds after lighter work the
+        clock is still settling (a 128-row pass was seen at 84 us there against 67 us sustained)."""
+        import time
         fn = self.sweep(lambda x: self.do_split_kernel(x, scored))
-        timed(fn, 1)
-        return timed(fn, max(1, loops)) * 1e3 / self.n_layers
+        t0 = time.perf_counter()
+        sweep_ms = timed(fn, 1)
+        while (time.perf_counter() - t0) * 1e3 < 40.0:
+            timed(fn, 1)
+        reps = max(1, loops, int(20.0 / max(sweep_ms, 1e-3)) + 1)
+        return timed(fn, reps) * 1e3 / self.n_layers
 
     def kernel_rooflines(self, kern_us):
         gbs = self.alg_bytes / (kern_us * 1e-6) / 1e9
